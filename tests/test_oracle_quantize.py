@@ -1,0 +1,271 @@
+"""Pins for the oracle's block quantiser (CPU only): hand-derived blocks, invariants
+of eq. (1), the axis conventions of App. D / App. C, and the indexing of the
+stochastic-rounding counter."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_09825_amd import synth
+
+
+def bf16_bits(a):
+    """float array (values exactly representable in bf16 or not) -> uint16 patterns, RNE."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
+    return synth.as_u16(t).copy()
+
+
+def bits_to_f64(u16):
+    return (u16.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def unpack(q):
+    lo, hi = q & 15, q >> 4
+    return np.stack([lo, hi], axis=-1).reshape(q.shape[0], -1)
+
+
+# ------------------------------------------------------------ hand-derived blocks
+def test_all_equal_block():
+    # 32 x 1.0: amax = 1 = 2^0 -> shared exponent 0 - 2 = -2 -> byte 125; 1.0 / 2^-2 = 4 -> code 6
+    q, s = oracle.quantize(bf16_bits(np.ones((1, 32))))
+    assert s.tolist() == [[125]]
+    assert q.tolist() == [[0x66] * 16]
+
+
+def test_single_outlier_block():
+    # 100, then 31 x 1.0: floor(log2 100) = 6 -> exponent 4 -> byte 131;
+    # 100/16 = 6.25 saturates to 6 (code 7); 1/16 = 0.0625 rounds to 0
+    x = np.ones((1, 32))
+    x[0, 0] = 100.0
+    q, s = oracle.quantize(bf16_bits(x))
+    assert s.tolist() == [[131]]
+    assert q.tolist() == [[0x07] + [0x00] * 15]
+
+
+def test_signed_block_and_nibble_order():
+    # amax 6 -> exponent 0 -> byte 127: values are their own codes
+    vals = [6, -6, 0.5, -0.5, 1, -1, 1.5, -1.5, 2, -2, 3, -3, 4, -4, 0, -0.0] + [0.0] * 16
+    q, s = oracle.quantize(bf16_bits(np.array([vals])))
+    assert s.tolist() == [[127]]
+    codes = [7, 15, 1, 9, 2, 10, 3, 11, 4, 12, 5, 13, 6, 14, 0, 8] + [0] * 16
+    want = [codes[i] | (codes[i + 1] << 4) for i in range(0, 32, 2)]  # even index -> low nibble
+    assert q.tolist() == [want]
+
+
+def test_zero_block_and_non_finite_block():
+    x = np.zeros((1, 64))
+    x[0, 40] = np.inf
+    q, s = oracle.quantize(bf16_bits(x))
+    assert s.tolist() == [[0, 0xFF]]
+    assert not q.any()
+    x[0, 40] = np.nan
+    q, s = oracle.quantize(bf16_bits(x))
+    assert s.tolist() == [[0, 0xFF]] and not q.any()
+
+
+def test_subnormal_scale_floor():
+    # amax = 2^-126 * 1.5 -> exponent field 1 -> byte clamps to 0 (2^-127): 1.5*2^-126 * 2^127 = 3
+    x = np.zeros((1, 32), dtype=np.float32)
+    x[0, 3] = np.float32(1.5 * 2.0**-126)
+    x[0, 4] = -np.float32(2.0**-127)  # bf16-representable subnormal: * 2^127 = 1
+    q, s = oracle.quantize(bf16_bits(x))
+    assert s.tolist() == [[0]]
+    codes = unpack(q)[0]
+    assert codes[3] == 5 and codes[4] == 10 and codes.sum() == 15
+
+
+# ------------------------------------------------------------ invariants of eq. (1)
+@pytest.fixture(scope="module")
+def x_normal():
+    return synth.as_u16(synth.normal(48, 256, 1.0, seed=11, stream=synth.STREAM_X)).copy()
+
+
+def test_idempotence(x_normal):
+    q, s = oracle.quantize(x_normal)
+    xhat = oracle.dequantize(q, s)
+    # reconstructed values have at most 2 significant bits: exactly representable in bf16
+    again = bf16_bits(xhat)
+    assert np.array_equal(bits_to_f64(again).reshape(xhat.shape), xhat)
+    q2, s2 = oracle.quantize(again)
+    assert np.array_equal(unpack(q2) & 7, unpack(q) & 7)            # magnitudes unchanged
+    nz = (unpack(q) & 7) != 0
+    assert np.array_equal((unpack(q2) >> 3)[nz], (unpack(q) >> 3)[nz])
+    # the scale can only differ where a whole block rounded to zero
+    blocks_nz = (unpack(q) & 7).reshape(q.shape[0], -1, 32).any(axis=2)
+    # a block whose maximum rounded *up* across a power of two keeps its scale only if the
+    # maximum code is < 8; with amax*2^-E in [4,8) it rounds to 4 or 6: same binade
+    assert np.array_equal(s2[blocks_nz], s[blocks_nz])
+
+
+def test_error_bound_of_the_format(x_normal):
+    q, s = oracle.quantize(x_normal)
+    x = bits_to_f64(x_normal).reshape(x_normal.shape)
+    xhat = oracle.dequantize(q, s)
+    E = np.repeat(s.astype(np.int64) - 127, 32, axis=1)
+    t = np.abs(x) / 2.0**E
+    assert (t < 8).all() and (t.reshape(t.shape[0], -1, 32).max(axis=2) >= 4).all()
+    delta = np.where(t < 2, 0.5, np.where(t < 4, 1.0, 2.0))
+    err = np.abs(x - xhat) / 2.0**E
+    unsat = t <= 6
+    assert (err[unsat] <= delta[unsat] / 2 + 1e-12).all()
+    assert (err[~unsat] < 2).all()
+    assert (np.sign(xhat) * np.sign(x) >= 0).all()
+
+
+def test_scale_invariance(x_normal):
+    q, s = oracle.quantize(x_normal)
+    for k in (-20, 7):
+        xs = bf16_bits(np.ldexp(bits_to_f64(x_normal), k).reshape(x_normal.shape))
+        qk, sk = oracle.quantize(xs)
+        assert np.array_equal(qk, q)
+        assert np.array_equal(sk.astype(np.int64), s.astype(np.int64) + k)
+
+
+def test_block_independence(x_normal):
+    q, s = oracle.quantize(x_normal)
+    y = x_normal.copy()
+    y[5, 64:96] = bf16_bits(np.full(32, 1000.0))
+    q2, s2 = oracle.quantize(y)
+    mask = np.ones_like(q, dtype=bool)
+    mask[5, 32:48] = False
+    assert np.array_equal(q2[mask], q[mask])
+    assert (s2[5, 2] != s[5, 2]) and np.array_equal(np.delete(s2[5], 2), np.delete(s[5], 2))
+
+
+# ------------------------------------------------------------ axes and strides
+@pytest.mark.parametrize("had", [oracle.HAD_NONE, oracle.HAD_DET, oracle.HAD_RANDSIGN, oracle.HAD_DET16])
+def test_axis_first_is_axis_last_of_the_transpose(had):
+    x = synth.as_u16(synth.normal(96, 80, 1.0, seed=4, stream=synth.STREAM_DY)).copy()
+    qf, sf = oracle.quantize(x, axis=oracle.AXIS_FIRST, had=had, seed=9)
+    ql, sl = oracle.quantize(np.ascontiguousarray(x.T), axis=oracle.AXIS_LAST, had=had, seed=9)
+    assert qf.shape == (80, 48) and sf.shape == (80, 3)
+    assert np.array_equal(qf, ql) and np.array_equal(sf, sl)
+
+
+def test_leading_dimension():
+    big = synth.as_u16(synth.normal(16, 160, 1.0, seed=6, stream=synth.STREAM_X)).copy()
+    view = big[:, 32:128]                       # ld = 160, cols = 96
+    q1, s1 = oracle.quantize(view)
+    q2, s2 = oracle.quantize(np.ascontiguousarray(view))
+    assert np.array_equal(q1, q2) and np.array_equal(s1, s2)
+
+
+def test_contraction_length_must_be_a_multiple_of_32():
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((4, 48), dtype=np.uint16))
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((48, 32), dtype=np.uint16), axis=oracle.AXIS_FIRST)
+
+
+# ------------------------------------------------------------ Hadamard modes
+def test_det_hadamard_on_columns_of_H():
+    # x = 2^a * (column j of the +-1 matrix): rotation concentrates it in element j:
+    # H x / sqrt(32) = sqrt(32) 2^a e_j = 5.657 * 2^a -> exponent a, 5.657 rounds to 6 (code 7)
+    H = np.array([[(-1) ** bin(i & j).count("1") for j in range(32)] for i in range(32)], dtype=np.float64)
+    for a, j in ((0, 0), (3, 5), (-6, 31), (10, 16)):
+        x = (2.0**a) * H[:, j]
+        q, s = oracle.quantize(bf16_bits(x[None, :]), had=oracle.HAD_DET)
+        codes = unpack(q)[0]
+        assert s.tolist() == [[127 + a]]
+        assert codes[j] == 7 and (np.delete(codes, j) & 7).sum() == 0
+
+
+def test_det_hadamard_spreads_a_spike():
+    # x = 32 e_j: H x / sqrt(32) = sqrt(32) * (+-1): every element 5.657 in magnitude -> all code 7,
+    # signs = column j of H; without rotation the spike is alone in its block
+    j = 13
+    x = np.zeros((1, 32))
+    x[0, j] = 32.0
+    q, s = oracle.quantize(bf16_bits(x), had=oracle.HAD_DET)
+    codes = unpack(q)[0]
+    assert s.tolist() == [[127]]
+    signs = np.array([bin(i & j).count("1") & 1 for i in range(32)])
+    assert np.array_equal(codes & 7, np.full(32, 7)) and np.array_equal(codes >> 3, signs)
+
+
+def test_det_hadamard_matches_float64_rotation_within_format_error():
+    x = synth.as_u16(synth.normal(32, 128, 1.0, seed=21, stream=synth.STREAM_X)).copy()
+    q, s = oracle.quantize(x, had=oracle.HAD_DET)
+    H = np.array([[(-1) ** bin(i & j).count("1") for j in range(32)] for i in range(32)], dtype=np.float64)
+    xr = (bits_to_f64(x).reshape(32, 4, 32) @ H / math.sqrt(32.0)).reshape(32, 128)
+    xhat = oracle.dequantize(q, s)
+    E = np.repeat(s.astype(np.int64) - 127, 32, axis=1)
+    t = np.abs(xr) / 2.0**E
+    delta = np.where(t < 2, 0.5, np.where(t < 4, 1.0, 2.0))
+    err = np.abs(xr - xhat) / 2.0**E
+    ok = t <= 6
+    assert (err[ok] <= delta[ok] / 2 + 1e-5).all() and (err[~ok] < 2 + 1e-5).all()
+    # and the rotation is norm-preserving: block energies agree to quantisation accuracy
+    assert abs((xhat**2).sum() / (bits_to_f64(x) ** 2).sum() - 1) < 0.05
+
+
+def test_det16_is_two_independent_16_point_rotations():
+    x = synth.as_u16(synth.normal(8, 64, 1.0, seed=22, stream=synth.STREAM_X)).copy()
+    q, s = oracle.quantize(x, had=oracle.HAD_DET16)
+    H16 = np.array([[(-1) ** bin(i & j).count("1") for j in range(16)] for i in range(16)], dtype=np.float64)
+    xr = (bits_to_f64(x).reshape(8, 4, 16) @ H16 / 4.0).reshape(8, 64)
+    xhat = oracle.dequantize(q, s)
+    E = np.repeat(s.astype(np.int64) - 127, 32, axis=1)
+    t = np.abs(xr) / 2.0**E
+    delta = np.where(t < 2, 0.5, np.where(t < 4, 1.0, 2.0))
+    err = np.abs(xr - xhat) / 2.0**E
+    ok = t <= 6
+    assert (err[ok] <= delta[ok] / 2 + 1e-5).all() and (err[~ok] < 2 + 1e-5).all()
+    assert (t.reshape(8, 2, 32).max(axis=2) >= 4 - 1e-5).all() and (t < 8 + 1e-5).all()
+
+
+def test_random_sign_is_det_hadamard_of_the_sign_flipped_input():
+    seed = 31337
+    x = synth.as_u16(synth.normal(16, 96, 1.0, seed=23, stream=synth.STREAM_X)).copy()
+    mask = oracle.sign_mask(seed)
+    flip = np.array([0x8000 if (mask >> (c % 32)) & 1 else 0 for c in range(96)], dtype=np.uint16)
+    q1, s1 = oracle.quantize(x, had=oracle.HAD_RANDSIGN, seed=seed)
+    q2, s2 = oracle.quantize(x ^ flip[None, :], had=oracle.HAD_DET)
+    assert np.array_equal(q1, q2) and np.array_equal(s1, s2)
+    q3, _ = oracle.quantize(x, had=oracle.HAD_RANDSIGN, seed=seed + 1)
+    assert not np.array_equal(q1, q3)
+    # the diagonal runs along the contraction axis also for AXIS_FIRST
+    xt = np.ascontiguousarray(x.T)  # [96][16] -> contraction over 96 rows
+    flip_rows = flip[:, None]
+    q4, s4 = oracle.quantize(xt, axis=oracle.AXIS_FIRST, had=oracle.HAD_RANDSIGN, seed=seed)
+    q5, s5 = oracle.quantize(xt ^ flip_rows, axis=oracle.AXIS_FIRST, had=oracle.HAD_DET)
+    assert np.array_equal(q4, q5) and np.array_equal(s4, s5)
+
+
+# ------------------------------------------------------------ stochastic rounding in tensors
+@pytest.mark.parametrize("axis", [oracle.AXIS_LAST, oracle.AXIS_FIRST])
+def test_sr_counter_is_the_output_linear_index(axis):
+    seed = 5
+    x = synth.as_u16(synth.normal(64, 96, 1.0, seed=24, stream=synth.STREAM_X)).copy()
+    q, s = oracle.quantize(x, axis=axis, rnd=oracle.SR, seed=seed)
+    _, s_rne = oracle.quantize(x, axis=axis)
+    assert np.array_equal(s, s_rne)                                  # the scale ignores the rounding mode
+    xv = bits_to_f64(x).reshape(x.shape)
+    if axis == oracle.AXIS_FIRST:
+        xv = xv.T
+    R, C = xv.shape
+    codes = unpack(q)
+    for r in range(0, R, 7):
+        for c in range(0, C, 5):
+            t = math.ldexp(xv[r, c], -(int(s[r, c // 32]) - 127))
+            assert codes[r, c] == oracle.e2m1_encode_sr(t, oracle.rand32(seed, r * C + c))
+
+
+def test_sr_brackets_and_differs_from_rne():
+    x = synth.as_u16(synth.normal(64, 128, 1.0, seed=25, stream=synth.STREAM_X)).copy()
+    q, s = oracle.quantize(x, rnd=oracle.SR, seed=1)
+    q0, _ = oracle.quantize(x)
+    xv = bits_to_f64(x).reshape(x.shape)
+    E = np.repeat(s.astype(np.int64) - 127, 32, axis=1)
+    t = np.minimum(np.abs(xv) / 2.0**E, 6.0)
+    delta = np.where(t < 2, 0.5, np.where(t < 4, 1.0, 2.0))
+    err = np.abs(np.abs(oracle.dequantize(q, s)) / 2.0**E - t)
+    assert (err < delta).all()
+    assert 0.2 < (q != q0).mean() < 0.9
+    assert not np.array_equal(q, oracle.quantize(x, rnd=oracle.SR, seed=2)[0])
+    assert np.array_equal(q, oracle.quantize(x, rnd=oracle.SR, seed=1)[0])
+    # mean error over many elements ~ 0 (unbiased), unlike the magnitude of RNE's worst case
+    signed_err = (np.abs(oracle.dequantize(q, s)) / 2.0**E - t)
+    assert abs(signed_err.mean()) < 4 * signed_err.std() / math.sqrt(signed_err.size)

@@ -1,0 +1,158 @@
+/*
+ * mxfp4.h -- C ABI of the MI355X (gfx950) MXFP4 linear-layer library.
+ *
+ * The library implements the hot path of MXFP4 pretraining: for each of the
+ * three GEMMs of a transformer linear layer (App. C.1 Fprop Y = X W^T, App. C.2
+ * Dgrad dX = dY W, App. C.3 Wgrad dW = dY^T X) both operands are optionally
+ * rotated by a block Hadamard transform (App. A.2), quantised to MXFP4 along
+ * the contraction axis (App. A.1, eq. (1)) and multiplied on the FP4 matrix
+ * units with fp32 accumulation.
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer on the current HIP device unless
+ *     stated otherwise.  The caller owns all buffers, including workspaces; the
+ *     library never allocates, frees or keeps a pointer after a call returns.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Calls only enqueue work on that stream and return; they never
+ *     synchronise.  Outputs are valid once the stream has reached that point.
+ *   - Return value: an mxfp4_status.  Argument errors are detected on the host
+ *     before anything is launched, so a failed call has no effect.  No call
+ *     throws or aborts.
+ *   - bf16 tensors are row-major with a leading dimension in elements.
+ *   - Quantised tensor layout ("canonical"): for an operand with R rows and
+ *     contraction length C (C % 32 == 0)
+ *         q: uint8 [R][C/2]   two E2M1 codes per byte; element c of a row is in
+ *                             byte c/2, even c in the low nibble
+ *         s: uint8 [R][C/32]  one E8M0 byte per 32 consecutive elements,
+ *                             value 2^(byte-127); 0xFF marks a block that held
+ *                             a NaN or an infinity (its codes are all 0)
+ *     Every GEMM is then out[i][j] = sum_c A[i][c] * B[j][c].
+ */
+#ifndef MXFP4_H
+#define MXFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MXFP4_OK = 0,
+    MXFP4_EINVAL = 1,     /* null pointer, unknown enum value, bad flag combination */
+    MXFP4_ESHAPE = 2,     /* a dimension <= 0, contraction length not a multiple of 32, ld too small */
+    MXFP4_EALIGN = 3,     /* pointer or leading dimension not aligned as documented */
+    MXFP4_EWORKSPACE = 4, /* workspace smaller than mxfp4_linear_workspace_bytes() */
+    MXFP4_EDEVICE = 5,    /* HIP reported an error at launch, or the device is not gfx950 */
+    MXFP4_ENOTIMPL = 6
+} mxfp4_status;
+
+/* Which axis of the row-major input the 32-element blocks run along (App. D). */
+typedef enum {
+    MXFP4_AXIS_LAST = 0, /* 1x32 blocks along a row:     R = rows, C = cols                      */
+    MXFP4_AXIS_FIRST = 1 /* 32x1 blocks down a column:   R = cols, C = rows; output is transposed */
+} mxfp4_axis;
+
+/* Rotation applied to every block before quantisation (App. A.2; Table 1 rows). */
+typedef enum {
+    MXFP4_HAD_NONE = 0,
+    MXFP4_HAD_DET = 1,      /* deterministic H32/sqrt(32), Sylvester order                       */
+    MXFP4_HAD_RANDSIGN = 2, /* H32/sqrt(32) after a seeded +-1 diagonal shared by all blocks     */
+    MXFP4_HAD_DET16 = 3     /* two independent H16/4 per block (the paper's H16 tiling)          */
+} mxfp4_hadamard;
+
+/* FP4 cast of eq. (1). */
+typedef enum {
+    MXFP4_RNE = 0, /* nearest, ties to the even code, saturating at +-6                              */
+    MXFP4_SR = 1   /* stochastic: counter hash of (seed, linear index of the element in q's layout) */
+} mxfp4_round;
+
+typedef enum { MXFP4_OUT_BF16 = 0, MXFP4_OUT_FP32 = 1 } mxfp4_out;
+
+/* Recipe of one linear layer (one row of Table 1: stabiliser x rounding, all stages MXFP4). */
+typedef struct {
+    int32_t hadamard;      /* mxfp4_hadamard, used for both operands of every GEMM             */
+    int32_t rounding;      /* mxfp4_round                                                       */
+    uint64_t seed;         /* random-sign diagonal and stochastic-rounding counters             */
+    int32_t y_dtype;       /* mxfp4_out for Y                                                   */
+    int32_t dx_dtype;      /* mxfp4_out for dX                                                  */
+    int32_t dw_dtype;      /* mxfp4_out for dW                                                  */
+    int32_t dw_accumulate; /* 1: dW += (fp32 only; gradient accumulation), 0: dW =             */
+} mxfp4_linear_cfg;
+
+/*
+ * Rotate + quantise one bf16 matrix (App. A.1 eq. (1), App. A.2, App. D).
+ *   x        bf16 [rows][ld], ld >= cols
+ *   axis     MXFP4_AXIS_LAST : R = rows, C = cols, cols % 32 == 0;
+ *                              x 16-byte aligned, ld % 8 == 0
+ *            MXFP4_AXIS_FIRST: R = cols, C = rows, rows % 32 == 0, cols % 2 == 0;
+ *                              x 4-byte aligned, ld % 2 == 0; q/s hold the quantised transpose
+ *   q_out    uint8 [R][C/2], 16-byte aligned      s_out  uint8 [R][C/32]
+ *   seed     used by MXFP4_HAD_RANDSIGN and MXFP4_SR only.  Both operands of a GEMM must
+ *            use the same seed and mode for the rotation to cancel in the product.
+ * Per block: widen to fp32; optional sign flips; fp32 butterflies in the order
+ * h = 1,2,4,8,16 then one multiply by fl32(2^-2.5) (H16: h = 1..8, multiply by 1/4);
+ * scale byte = clamp(biased exponent of the block maximum - 2, 0, 254); codes = FP4 cast of
+ * value * 2^-(byte-127).  Stochastic rounding draws u = (2*(r>>9)+1)/2^24 from the 32-bit
+ * counter hash r of (seed, row_of_q * C + column_of_q) and rounds up when u < fraction.
+ * rows == 0 or cols == 0 is a valid empty call.
+ */
+int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int axis, int hadamard,
+                   int rounding, uint64_t seed, void *q_out, void *s_out, void *hip_stream);
+
+/*
+ * Block-scaled FP4 GEMM on quantised operands (the MXFP4 GEMM that replaces the FP8 GEMM of
+ * the linear layers, Sec. 1 and App. A.2):
+ *     out[i][j] (+)= sum_c A[i][c] * B[j][c],  A = a_q/a_s [R_a][C],  B = b_q/b_s [R_b][C]
+ * products exact, fp32 accumulation.  C % 32 == 0; R_a, R_b >= 0 (0 = empty call).
+ *   out        [R_a][ld_out] bf16 or fp32 (out_dtype), ld_out >= R_b
+ *   accumulate 1: out += result (MXFP4_OUT_FP32 only), 0: out = result
+ * All operand pointers 16-byte aligned.  A scale byte of 0xFF yields NaN outputs.
+ */
+int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_s, int64_t R_a, int64_t R_b,
+               int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream);
+
+/*
+ * Fprop of one linear layer (App. C.1): Y[M][N] = Q(X H) Q(W H)^T, contraction over K.
+ *   x bf16 [M][K], w bf16 [N][K] (both dense: ld = K), y [M][N] dense, dtype cfg->y_dtype
+ *   workspace: device scratch of at least mxfp4_linear_workspace_bytes(M,N,K,cfg,0) bytes,
+ *   256-byte aligned.  On return (after the stream completes) it holds the canonical
+ *   q/s of X then W at the offsets reported by mxfp4_linear_workspace_layout.
+ * M, N, K >= 1 and K % 32 == 0 (else MXFP4_ESHAPE).
+ */
+int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N, int64_t K,
+                     const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward of one linear layer: Dgrad (App. C.2) dX[M][K] = Q(dY H) Q(W^T H)^T, contraction
+ * over N, and Wgrad (App. C.3) dW[N][K] = Q(dY^T H) Q(X^T H)^T, contraction over tokens M.
+ *   dy bf16 [M][N], x bf16 [M][K], w bf16 [N][K], all dense.
+ *   dx or dw may be NULL to skip that GEMM (x may be NULL if dw is, w if dx is).
+ *   M, N, K >= 1; N % 8 == 0 and K % 8 == 0 (16-byte rows); Dgrad needs N % 32 == 0, Wgrad
+ *   needs M % 32 == 0.
+ *   workspace as for the forward call, sized with bwd = 1.
+ */
+int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw, int64_t M, int64_t N,
+                     int64_t K, const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
+
+/* Bytes of workspace the fused calls need (bwd = 0: forward, 1: backward).  Host-only. */
+size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd);
+
+/*
+ * Byte offsets, inside the workspace, of the canonical quantised operands the fused calls
+ * leave behind (for byte-parity tests).  offsets[8] receives, in order, q and s of:
+ *   bwd = 0: X (rows M, C=K), W (rows N, C=K); entries 4..7 are 0
+ *   bwd = 1: dY (rows M, C=N), W^T (rows K, C=N), dY^T (rows N, C=M), X^T (rows K, C=M)
+ * Host-only.  Returns MXFP4_OK or MXFP4_EINVAL.
+ */
+int mxfp4_linear_workspace_layout(int64_t M, int64_t N, int64_t K, int bwd, size_t offsets[8]);
+
+/* Human-readable name of a status code; pointer to static storage, never NULL.  Host-only. */
+const char *mxfp4_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MXFP4_H */

@@ -1,0 +1,178 @@
+"""Python binding of libmxfp4.so (the gfx950 MXFP4 linear-layer library).
+
+Argument marshalling only: every function here forwards to the C-ABI entry point
+of the same name (include/mxfp4.h) with raw device pointers and the current torch
+stream; torch is used for device memory and streams and for nothing else.  There is
+no fallback: if the HIP library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmxfp4.so")
+
+# enums of include/mxfp4.h
+OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EDEVICE, ENOTIMPL = range(7)
+AXIS_LAST, AXIS_FIRST = 0, 1
+HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16 = 0, 1, 2, 3
+RNE, SR = 0, 1
+OUT_BF16, OUT_FP32 = 0, 1
+
+EXPORTS = ("mxfp4_quantize", "mxfp4_gemm", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
+           "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout", "mxfp4_status_string")
+
+
+class LinearCfg(ctypes.Structure):
+    """mxfp4_linear_cfg"""
+    _fields_ = [("hadamard", ctypes.c_int32), ("rounding", ctypes.c_int32), ("seed", ctypes.c_uint64),
+                ("y_dtype", ctypes.c_int32), ("dx_dtype", ctypes.c_int32), ("dw_dtype", ctypes.c_int32),
+                ("dw_accumulate", ctypes.c_int32)]
+
+
+class Mxfp4Error(RuntimeError):
+    def __init__(self, call: str, status: int):
+        self.status = status
+        super().__init__(f"{call} failed: status {status} ({status_string(status)})")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmxfp4.so (built by paper_2605_09825_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2605_09825_amd.build` (there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci, u64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint64, ctypes.c_size_t
+        L.mxfp4_quantize.restype = ci
+        L.mxfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, u64, vp, vp, vp]
+        L.mxfp4_gemm.restype = ci
+        L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
+        L.mxfp4_linear_fwd.restype = ci
+        L.mxfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
+        L.mxfp4_linear_bwd.restype = ci
+        L.mxfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
+        L.mxfp4_linear_workspace_bytes.restype = sz
+        L.mxfp4_linear_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(LinearCfg), ci]
+        L.mxfp4_linear_workspace_layout.restype = ci
+        L.mxfp4_linear_workspace_layout.argtypes = [i64, i64, i64, ci, ctypes.POINTER(sz)]
+        L.mxfp4_status_string.restype = ctypes.c_char_p
+        L.mxfp4_status_string.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mxfp4_status_string(int(status)).decode()
+
+
+def _check(call: str, status: int) -> None:
+    if status != OK:
+        raise Mxfp4Error(call, status)
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _out_dtype(code: int):
+    import torch
+    return torch.float32 if code == OUT_FP32 else torch.bfloat16
+
+
+# ---------------------------------------------------------------------------------------
+def mxfp4_quantize(x, axis: int = AXIS_LAST, hadamard: int = HAD_NONE, rounding: int = RNE, seed: int = 0,
+                   q=None, s=None, stream=None) -> Tuple["torch.Tensor", "torch.Tensor"]:
+    """x: bf16 CUDA tensor [rows][cols] with unit inner stride.  Returns (q, s) uint8 tensors
+    [R][C/2] and [R][C/32] (allocated here with torch.empty unless passed in)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and (x.numel() == 0 or x.stride(1) == 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, x.stride(0))
+    R, C = (rows, cols) if axis == AXIS_LAST else (cols, rows)
+    if q is None:
+        q = torch.empty((R, C // 2), dtype=torch.uint8, device=x.device)
+    if s is None:
+        s = torch.empty((R, C // 32), dtype=torch.uint8, device=x.device)
+    _check("mxfp4_quantize", lib().mxfp4_quantize(_ptr(x), rows, cols, ld, axis, hadamard, rounding,
+                                                  seed & (2**64 - 1), _ptr(q), _ptr(s), _stream_ptr(stream)))
+    return q, s
+
+
+def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumulate: bool = False, stream=None):
+    """out[i][j] (+)= sum_c A[i][c] B[j][c] on canonical quantised operands (uint8 CUDA tensors)."""
+    import torch
+    Ra, C = a_q.shape[0], a_q.shape[1] * 2
+    Rb = b_q.shape[0]
+    assert b_q.shape[1] * 2 == C and a_q.is_contiguous() and b_q.is_contiguous()
+    assert a_s.is_contiguous() and b_s.is_contiguous()
+    if out is None:
+        out = torch.empty((Ra, Rb), dtype=_out_dtype(out_dtype), device=a_q.device)
+    assert out.dtype == _out_dtype(out_dtype) and (out.numel() == 0 or out.stride(1) == 1)
+    ld = out.stride(0) if Ra > 1 else max(Rb, out.stride(0))
+    _check("mxfp4_gemm", lib().mxfp4_gemm(_ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), Ra, Rb, C, _ptr(out), ld,
+                                          out_dtype, int(accumulate), _stream_ptr(stream)))
+    return out
+
+
+def mxfp4_linear_workspace_bytes(M: int, N: int, K: int, cfg: LinearCfg, bwd: bool) -> int:
+    return int(lib().mxfp4_linear_workspace_bytes(M, N, K, ctypes.byref(cfg), int(bwd)))
+
+
+def mxfp4_linear_workspace_layout(M: int, N: int, K: int, bwd: bool):
+    arr = (ctypes.c_size_t * 8)()
+    _check("mxfp4_linear_workspace_layout", lib().mxfp4_linear_workspace_layout(M, N, K, int(bwd), arr))
+    return [int(v) for v in arr]
+
+
+def make_cfg(hadamard: int = HAD_NONE, rounding: int = RNE, seed: int = 0, y_dtype: int = OUT_BF16,
+             dx_dtype: int = OUT_BF16, dw_dtype: int = OUT_FP32, dw_accumulate: bool = False) -> LinearCfg:
+    return LinearCfg(hadamard, rounding, seed & (2**64 - 1), y_dtype, dx_dtype, dw_dtype, int(dw_accumulate))
+
+
+def mxfp4_linear_fwd(x, w, cfg: LinearCfg, y=None, workspace=None, stream=None):
+    """Y = Q(X H) Q(W H)^T.  x [M][K], w [N][K] bf16 CUDA, contiguous.  Returns (y, workspace)."""
+    import torch
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and x.is_contiguous() and w.is_contiguous()
+    need = mxfp4_linear_workspace_bytes(M, N, K, cfg, False)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if y is None:
+        y = torch.empty((M, N), dtype=_out_dtype(cfg.y_dtype), device=x.device)
+    _check("mxfp4_linear_fwd", lib().mxfp4_linear_fwd(_ptr(x), _ptr(w), _ptr(y), M, N, K, ctypes.byref(cfg),
+                                                      _ptr(workspace), workspace.numel(), _stream_ptr(stream)))
+    return y, workspace
+
+
+def mxfp4_linear_bwd(dy, x, w, cfg: LinearCfg, dx=None, dw=None, need_dx: bool = True, need_dw: bool = True,
+                     workspace=None, stream=None):
+    """dX = Q(dY H) Q(W^T H)^T and dW = Q(dY^T H) Q(X^T H)^T.  Returns (dx, dw, workspace)."""
+    import torch
+    M, N = dy.shape
+    K = x.shape[1] if x is not None else w.shape[1]
+    need = mxfp4_linear_workspace_bytes(M, N, K, cfg, True)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dy.device)
+    if need_dx and dx is None:
+        dx = torch.empty((M, K), dtype=_out_dtype(cfg.dx_dtype), device=dy.device)
+    if need_dw and dw is None:
+        assert not cfg.dw_accumulate, "accumulating into dW needs the caller's dW"
+        dw = torch.empty((N, K), dtype=_out_dtype(cfg.dw_dtype), device=dy.device)
+    _check("mxfp4_linear_bwd", lib().mxfp4_linear_bwd(_ptr(dy), _ptr(x), _ptr(w), _ptr(dx) if need_dx else None,
+                                                      _ptr(dw) if need_dw else None, M, N, K, ctypes.byref(cfg),
+                                                      _ptr(workspace), workspace.numel(), _stream_ptr(stream)))
+    return dx, dw, workspace

@@ -1,0 +1,248 @@
+// C ABI of the library (see include/mxfp4.h): argument checks on the host, then launches.
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include "../../include/mxfp4.h"
+#include "mxfp4_internal.h"
+
+namespace {
+
+using namespace mxfp4;
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// The kernels are built for gfx950 only: refuse to launch anywhere else (checked once per process
+// and device).
+int device_ok()
+{
+    static int cached[64];  // 0 unknown, 1 ok, 2 bad
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+        cached[dev] = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
+    }
+    return cached[dev] == 1;
+}
+
+int check_quantize(const void *x, int64_t rows, int64_t cols, int64_t ld, int axis, int had, int rnd,
+                   const void *q, const void *s)
+{
+    if (axis != MXFP4_AXIS_LAST && axis != MXFP4_AXIS_FIRST) return MXFP4_EINVAL;
+    if (had < MXFP4_HAD_NONE || had > MXFP4_HAD_DET16) return MXFP4_EINVAL;
+    if (rnd != MXFP4_RNE && rnd != MXFP4_SR) return MXFP4_EINVAL;
+    if (rows < 0 || cols < 0) return MXFP4_ESHAPE;
+    if (rows == 0 || cols == 0) return MXFP4_OK;
+    if (!x || !q || !s) return MXFP4_EINVAL;
+    if (ld < cols) return MXFP4_ESHAPE;
+    if (axis == MXFP4_AXIS_LAST && (cols % 32) != 0) return MXFP4_ESHAPE;
+    if (axis == MXFP4_AXIS_FIRST && ((rows % 32) != 0 || (cols % 2) != 0)) return MXFP4_ESHAPE;
+    if (rows > (int64_t(1) << 40) || cols > (int64_t(1) << 40)) return MXFP4_ESHAPE;
+    {   // the 1-D launch grids hold at most 2^31 - 1 workgroups
+        const int64_t groups = (axis == MXFP4_AXIS_LAST) ? (rows * (cols / 32) + 255) / 256
+                                                         : ((cols + 127) / 128) * ((rows / 32 + 7) / 8);
+        if (groups >= (int64_t(1) << 31)) return MXFP4_ESHAPE;
+    }
+    if (!aligned(q, 16)) return MXFP4_EALIGN;
+    if (axis == MXFP4_AXIS_LAST && (!aligned(x, 16) || (ld % 8) != 0)) return MXFP4_EALIGN;
+    if (axis == MXFP4_AXIS_FIRST && (!aligned(x, 4) || (ld % 2) != 0)) return MXFP4_EALIGN;
+    return -1;  // go
+}
+
+int check_gemm(const void *aq, const void *as, const void *bq, const void *bs, int64_t Ra, int64_t Rb, int64_t C,
+               const void *out, int64_t ld, int dt, int acc)
+{
+    if (dt != MXFP4_OUT_BF16 && dt != MXFP4_OUT_FP32) return MXFP4_EINVAL;
+    if (acc != 0 && acc != 1) return MXFP4_EINVAL;
+    if (acc == 1 && dt != MXFP4_OUT_FP32) return MXFP4_EINVAL;
+    if (Ra < 0 || Rb < 0 || C < 0 || (C % 32) != 0) return MXFP4_ESHAPE;
+    if (Ra == 0 || Rb == 0) return MXFP4_OK;
+    if (!out) return MXFP4_EINVAL;
+    if (ld < Rb) return MXFP4_ESHAPE;
+    if (C > 0 && (!aq || !as || !bq || !bs)) return MXFP4_EINVAL;
+    if (Ra > (int64_t(1) << 36) || Rb > (int64_t(65535) * 64)) return MXFP4_ESHAPE;
+    if (!aligned(aq, 16) || !aligned(bq, 16) || !aligned(out, 16)) return MXFP4_EALIGN;
+    return -1;
+}
+
+struct FwdLayout {
+    size_t xq, xs, wq, ws, total;
+};
+FwdLayout fwd_layout(int64_t M, int64_t N, int64_t K)
+{
+    FwdLayout L;
+    size_t o = 0;
+    L.xq = o; o = round_up(o + (size_t)M * (K / 2), 256);
+    L.xs = o; o = round_up(o + (size_t)M * (K / 32), 256);
+    L.wq = o; o = round_up(o + (size_t)N * (K / 2), 256);
+    L.ws = o; o = round_up(o + (size_t)N * (K / 32), 256);
+    L.total = o;
+    return L;
+}
+
+struct BwdLayout {
+    size_t gq, gs, wtq, wts, gtq, gts, xtq, xts, total;
+};
+BwdLayout bwd_layout(int64_t M, int64_t N, int64_t K)
+{
+    BwdLayout L;
+    size_t o = 0;
+    L.gq = o;  o = round_up(o + (size_t)M * (N / 2), 256);
+    L.gs = o;  o = round_up(o + (size_t)M * (N / 32), 256);
+    L.wtq = o; o = round_up(o + (size_t)K * (N / 2), 256);
+    L.wts = o; o = round_up(o + (size_t)K * (N / 32), 256);
+    L.gtq = o; o = round_up(o + (size_t)N * (M / 2), 256);
+    L.gts = o; o = round_up(o + (size_t)N * (M / 32), 256);
+    L.xtq = o; o = round_up(o + (size_t)K * (M / 2), 256);
+    L.xts = o; o = round_up(o + (size_t)K * (M / 32), 256);
+    L.total = o;
+    return L;
+}
+
+int check_cfg(const mxfp4_linear_cfg *cfg)
+{
+    if (!cfg) return MXFP4_EINVAL;
+    if (cfg->hadamard < MXFP4_HAD_NONE || cfg->hadamard > MXFP4_HAD_DET16) return MXFP4_EINVAL;
+    if (cfg->rounding != MXFP4_RNE && cfg->rounding != MXFP4_SR) return MXFP4_EINVAL;
+    const int32_t dts[3] = {cfg->y_dtype, cfg->dx_dtype, cfg->dw_dtype};
+    for (int i = 0; i < 3; ++i)
+        if (dts[i] != MXFP4_OUT_BF16 && dts[i] != MXFP4_OUT_FP32) return MXFP4_EINVAL;
+    if (cfg->dw_accumulate != 0 && cfg->dw_accumulate != 1) return MXFP4_EINVAL;
+    if (cfg->dw_accumulate == 1 && cfg->dw_dtype != MXFP4_OUT_FP32) return MXFP4_EINVAL;
+    return MXFP4_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mxfp4_status_string(int status)
+{
+    switch (status) {
+        case MXFP4_OK: return "ok";
+        case MXFP4_EINVAL: return "invalid argument (null pointer, unknown enum value or flag combination)";
+        case MXFP4_ESHAPE: return "bad shape (negative size, contraction length not a multiple of 32, ld too small)";
+        case MXFP4_EALIGN: return "misaligned pointer or leading dimension";
+        case MXFP4_EWORKSPACE: return "workspace too small";
+        case MXFP4_EDEVICE: return "HIP launch error or device is not gfx950";
+        case MXFP4_ENOTIMPL: return "not implemented";
+        default: return "unknown status";
+    }
+}
+
+int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int axis, int hadamard,
+                   int rounding, uint64_t seed, void *q_out, void *s_out, void *hip_stream)
+{
+    int rc = check_quantize(x_bf16, rows, cols, ld_elems, axis, hadamard, rounding, q_out, s_out);
+    if (rc >= 0) return rc;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    QuantArgs a{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
+                static_cast<uint8_t *>(q_out), static_cast<uint8_t *>(s_out)};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = (axis == MXFP4_AXIS_LAST) ? launch_quantize_rows(a, st) : launch_quantize_cols(a, st);
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
+int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_s, int64_t R_a, int64_t R_b,
+               int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream)
+{
+    int rc = check_gemm(a_q, a_s, b_q, b_s, R_a, R_b, C, out, ld_out, out_dtype, accumulate);
+    if (rc >= 0) return rc;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    GemmArgs g{static_cast<const uint8_t *>(a_q), static_cast<const uint8_t *>(a_s),
+               static_cast<const uint8_t *>(b_q), static_cast<const uint8_t *>(b_s),
+               R_a, R_b, C, out, ld_out, out_dtype == MXFP4_OUT_FP32, accumulate};
+    hipError_t e = launch_gemm(g, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
+size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd)
+{
+    (void)cfg;
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return bwd ? bwd_layout(M, N, K).total : fwd_layout(M, N, K).total;
+}
+
+int mxfp4_linear_workspace_layout(int64_t M, int64_t N, int64_t K, int bwd, size_t offsets[8])
+{
+    if (!offsets || M < 0 || N < 0 || K < 0) return MXFP4_EINVAL;
+    if (bwd) {
+        BwdLayout L = bwd_layout(M, N, K);
+        const size_t o[8] = {L.gq, L.gs, L.wtq, L.wts, L.gtq, L.gts, L.xtq, L.xts};
+        memcpy(offsets, o, sizeof(o));
+    } else {
+        FwdLayout L = fwd_layout(M, N, K);
+        const size_t o[8] = {L.xq, L.xs, L.wq, L.ws, 0, 0, 0, 0};
+        memcpy(offsets, o, sizeof(o));
+    }
+    return MXFP4_OK;
+}
+
+int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N, int64_t K,
+                     const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_cfg(cfg);
+    if (rc != MXFP4_OK) return rc;
+    if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0) return MXFP4_ESHAPE;
+    if (!x || !w || !y || !workspace) return MXFP4_EINVAL;
+    const FwdLayout L = fwd_layout(M, N, K);
+    if (workspace_bytes < L.total) return MXFP4_EWORKSPACE;
+    if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return MXFP4_EALIGN;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    rc = mxfp4_quantize(x, M, K, K, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.xq, ws + L.xs,
+                        hip_stream);
+    if (rc != MXFP4_OK) return rc;
+    rc = mxfp4_quantize(w, N, K, K, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.wq, ws + L.ws,
+                        hip_stream);
+    if (rc != MXFP4_OK) return rc;
+    return mxfp4_gemm(ws + L.xq, ws + L.xs, ws + L.wq, ws + L.ws, M, N, K, y, N, cfg->y_dtype, 0, hip_stream);
+}
+
+int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw, int64_t M, int64_t N,
+                     int64_t K, const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes,
+                     void *hip_stream)
+{
+    int rc = check_cfg(cfg);
+    if (rc != MXFP4_OK) return rc;
+    if (M <= 0 || N <= 0 || K <= 0) return MXFP4_ESHAPE;
+    if (dx && ((N % 32) != 0 || (K % 2) != 0)) return MXFP4_ESHAPE;
+    if (dw && ((M % 32) != 0 || (N % 2) != 0 || (K % 2) != 0)) return MXFP4_ESHAPE;
+    if (!dx && !dw) return MXFP4_OK;
+    if (!dy || !workspace) return MXFP4_EINVAL;
+    if ((dx && !w) || (dw && !x)) return MXFP4_EINVAL;
+    const BwdLayout L = bwd_layout(M, N, K);
+    if (workspace_bytes < L.total) return MXFP4_EWORKSPACE;
+    if (!aligned(workspace, 256) || !aligned(dy, 16) || (dx && (!aligned(dx, 16) || !aligned(w, 16))) ||
+        (dw && (!aligned(dw, 16) || !aligned(x, 16))))
+        return MXFP4_EALIGN;
+    if ((N % 8) != 0 || (K % 8) != 0) return MXFP4_EALIGN;  // dense bf16 rows must stay 16-byte aligned
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    if (dx) {
+        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq,
+                            ws + L.gs, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+        rc = mxfp4_quantize(w, N, K, K, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.wtq,
+                            ws + L.wts, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+        rc = mxfp4_gemm(ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+    }
+    if (dw) {
+        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gtq,
+                            ws + L.gts, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+        rc = mxfp4_quantize(x, M, K, K, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.xtq,
+                            ws + L.xts, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+        rc = mxfp4_gemm(ws + L.gtq, ws + L.gts, ws + L.xtq, ws + L.xts, N, K, M, dw, K, cfg->dw_dtype,
+                        cfg->dw_accumulate, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+    }
+    return MXFP4_OK;
+}
+
+}  // extern "C"

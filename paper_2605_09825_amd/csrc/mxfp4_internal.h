@@ -1,0 +1,33 @@
+// Internal launch interface between the C ABI (api.hip) and the gfx950 kernels.
+// Every launcher assumes its arguments were validated by the caller and returns the
+// hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mxfp4 {
+
+struct QuantArgs {
+    const uint16_t *x;  // bf16 [rows][ld]
+    int64_t rows, cols, ld;
+    int hadamard, rounding;
+    uint64_t seed;
+    uint8_t *q, *s;
+};
+
+// blocks along rows (1x32): q[rows][cols/2], s[rows][cols/32]
+hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st);
+// blocks down columns (32x1): q[cols][rows/2], s[cols][rows/32]
+hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st);
+
+struct GemmArgs {
+    const uint8_t *aq, *as, *bq, *bs;
+    int64_t Ra, Rb, C;
+    void *out;
+    int64_t ld;
+    int out_fp32, accumulate;
+};
+
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);
+
+}  // namespace mxfp4

@@ -1,0 +1,318 @@
+// Fused rotate + amax + scale + pack kernels for gfx950 (MXFP4 quantiser).
+//
+// What is computed per 32-element block is eq. (1) of App. A.1 with the OCP MX scale
+// rule, preceded by the Hadamard rotation of App. A.2; the block geometry is the
+// 1x32 (row-wise) and 32x1 (column-wise) layouts of App. D.
+//
+// Design: the work is HBM-bound (2 bytes read, 0.53 bytes written per element), so
+// each lane owns one whole block in registers: the five butterfly stages, the block
+// maximum, the scale and the packing need no cross-lane traffic at all, and the
+// packed output of a lane is one 16-byte store.
+//   * row-wise: a lane reads its 64 contiguous bytes with four 16-byte loads; lanes
+//     of a wave cover 4 KiB of contiguous memory, so every fetched line is used.
+//   * column-wise: a lane owns two adjacent columns over 32 rows (32 dword loads,
+//     256 contiguous bytes per wave and row); the eight waves of a workgroup take
+//     eight consecutive row blocks, and the packed codes are regrouped through LDS
+//     so that each output row receives 128 contiguous bytes.
+#include "mxfp4_internal.h"
+
+namespace mxfp4 {
+namespace {
+
+constexpr int HAD_NONE = 0, HAD_DET = 1, HAD_RANDSIGN = 2, HAD_DET16 = 3;
+constexpr int RND_RNE = 0, RND_SR = 1;
+
+// ---- counter hash: stateless 32-bit mixer applied to (seed, index) -----------------
+struct RngKey {
+    uint32_t seed_lo_mul;  // low seed word times the odd constant
+    uint32_t seed_hi_mix;  // mixed high seed word
+};
+
+__host__ __device__ __forceinline__ uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x9E3779B9u;
+    x ^= x >> 15;
+    x *= 0xBB67AE85u;
+    x ^= x >> 16;
+    return x;
+}
+
+__host__ __device__ __forceinline__ uint32_t rand32(RngKey k, uint64_t idx)
+{
+    return mix32(mix32((uint32_t)idx + k.seed_lo_mul) ^ (uint32_t)(idx >> 32) ^ k.seed_hi_mix);
+}
+
+RngKey make_key(uint64_t seed)
+{
+    RngKey k;
+    k.seed_lo_mul = (uint32_t)seed * 0x9E3779B9u;
+    k.seed_hi_mix = mix32((uint32_t)(seed >> 32) ^ 0x6A09E667u);
+    return k;
+}
+
+// ---- one block in registers ---------------------------------------------------------
+template <int N>
+__device__ __forceinline__ void butterflies(float (&v)[32])
+{
+#pragma unroll
+    for (int h = 1; h < N; h <<= 1) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            if ((i & h) == 0) {
+                float a = v[i], b = v[i + h];
+                v[i] = a + b;
+                v[i + h] = a - b;
+            }
+        }
+    }
+}
+
+// Stochastic rounding of |t| (already divided by the block scale) to an E2M1 magnitude code.
+__device__ __forceinline__ uint32_t sr_code(float t, uint32_t r)
+{
+    float a = fminf(fabsf(t), 6.0f);
+    bool lo = a < 2.0f, mid = a < 4.0f;
+    float inv_delta = lo ? 2.0f : (mid ? 1.0f : 0.5f);
+    float q = a * inv_delta;  // exact: power-of-two factor
+    float fl = floorf(q);
+    float f = q - fl;  // exact
+    float u = (float)(2u * (r >> 9) + 1u) * 0x1p-24f;  // odd multiple of 2^-24 below 1: exact
+    uint32_t m = (uint32_t)fl + ((u < f) ? 1u : 0u);
+    uint32_t code = m + (lo ? 0u : (mid ? 2u : 4u));
+    return code | ((__float_as_uint(t) >> 28) & 8u);
+}
+
+// v: the block widened to fp32, in contraction order.  idx0: linear index of element 0
+// in the quantised output (stochastic rounding counter).
+template <int HAD, int RND>
+__device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask, RngKey key, uint64_t idx0,
+                                             uint4 &codes, uint32_t &scale_byte)
+{
+    if (HAD == HAD_RANDSIGN) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+            v[i] = __uint_as_float(__float_as_uint(v[i]) ^ (((sign_mask >> i) & 1u) << 31));
+    }
+    if (HAD == HAD_DET || HAD == HAD_RANDSIGN) {
+        butterflies<32>(v);
+        const float c = __uint_as_float(0x3E3504F3u);  // 2^-2.5 rounded to fp32
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = v[i] * c;
+    } else if (HAD == HAD_DET16) {
+        butterflies<16>(v);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = v[i] * 0.25f;
+    }
+
+    // block maximum on the bit patterns: NaN and infinity compare above every finite value
+    uint32_t amax = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        uint32_t b = __float_as_uint(v[i]) & 0x7FFFFFFFu;
+        amax = b > amax ? b : amax;
+    }
+    uint32_t eb = amax >> 23;
+    bool bad = (eb == 255u);
+    uint32_t sb = eb > 2u ? eb - 2u : 0u;  // eb <= 254 here, so sb <= 252
+    scale_byte = bad ? 0xFFu : sb;
+
+    uint32_t w[4];
+    if (RND == RND_RNE) {
+        // The converter divides by 2^(exponent field of `scale` - 127), rounds to nearest
+        // even on the E2M1 grid and saturates at 6; it writes one byte (two codes) per issue.
+        float scale = __uint_as_float(sb << 23);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t r = 0;
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 0], v[8 * j + 1], scale, 0);
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 2], v[8 * j + 3], scale, 1);
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 4], v[8 * j + 5], scale, 2);
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 6], v[8 * j + 7], scale, 3);
+            w[j] = r;
+        }
+    } else {
+        float inv = __uint_as_float((254u - sb) << 23);  // 2^-(sb-127); field in [2,254]
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t r = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int i = 8 * j + e;
+                uint32_t code = sr_code(v[i] * inv, rand32(key, idx0 + (uint64_t)i));
+                r |= code << (4 * e);
+            }
+            w[j] = r;
+        }
+    }
+    codes = bad ? make_uint4(0, 0, 0, 0) : make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// ---- row-wise (1x32) ---------------------------------------------------------------------
+// One lane per block.  nblocks = rows * (cols/32); block g is row g / bpr, column block g % bpr.
+template <int HAD, int RND>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t nblocks,
+                                                            int64_t bpr, int64_t ld, int dense,
+                                                            uint32_t sign_mask, RngKey key,
+                                                            uint8_t *__restrict__ q, uint8_t *__restrict__ s)
+{
+    int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= nblocks) return;
+    const uint16_t *src;
+    if (dense) {
+        src = x + g * 32;
+    } else {
+        int64_t row = g / bpr;
+        src = x + row * ld + (g - row * bpr) * 32;
+    }
+    const uint4 *p = reinterpret_cast<const uint4 *>(src);
+    uint4 raw[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) raw[j] = p[j];
+    float v[32];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        v[8 * j + 0] = bf16_lo(raw[j].x);
+        v[8 * j + 1] = bf16_hi(raw[j].x);
+        v[8 * j + 2] = bf16_lo(raw[j].y);
+        v[8 * j + 3] = bf16_hi(raw[j].y);
+        v[8 * j + 4] = bf16_lo(raw[j].z);
+        v[8 * j + 5] = bf16_hi(raw[j].z);
+        v[8 * j + 6] = bf16_lo(raw[j].w);
+        v[8 * j + 7] = bf16_hi(raw[j].w);
+    }
+    uint4 codes;
+    uint32_t sb;
+    encode_block<HAD, RND>(v, sign_mask, key, (uint64_t)g * 32u, codes, sb);
+    reinterpret_cast<uint4 *>(q)[g] = codes;
+    s[g] = (uint8_t)sb;
+}
+
+// ---- column-wise (32x1) ------------------------------------------------------------------
+// Workgroup tile: 256 rows (8 row blocks, one per wave) x 128 columns (2 per lane).
+constexpr int CT_COLS = 128, CT_RB = 8;
+
+template <int HAD, int RND>
+__global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t rows,
+                                                            int64_t cols, int64_t ld, uint32_t sign_mask,
+                                                            RngKey key, uint8_t *__restrict__ q,
+                                                            uint8_t *__restrict__ s, int s_vec8,
+                                                            uint32_t col_groups)
+{
+    __shared__ uint4 lds_q[CT_RB][CT_COLS + 1];
+    __shared__ __attribute__((aligned(8))) uint8_t lds_s[CT_COLS][CT_RB];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t by = blockIdx.x / col_groups, bx = blockIdx.x - by * col_groups;
+    const int64_t c0 = (int64_t)bx * CT_COLS;
+    const int64_t rb0 = (int64_t)by * CT_RB;
+    const int64_t nrb = rows >> 5;
+    const int64_t rb = rb0 + w;
+    const int64_t col = c0 + 2 * lane;
+    const bool active = (rb < nrb) && (col < cols);
+
+    uint32_t raw[32];
+    if (active) {
+        const uint16_t *p = x + (rb * 32) * ld + col;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint32_t *>(p + i * ld);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) raw[i] = 0;
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        float v[32];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = j == 0 ? bf16_lo(raw[i]) : bf16_hi(raw[i]);
+        uint4 codes;
+        uint32_t sb;
+        encode_block<HAD, RND>(v, sign_mask, key, (uint64_t)(col + j) * (uint64_t)rows + (uint64_t)rb * 32u,
+                               codes, sb);
+        lds_q[w][2 * lane + j] = codes;
+        lds_s[2 * lane + j][w] = (uint8_t)sb;
+    }
+    __syncthreads();
+
+    // each output row (input column) receives its 8 x 16 bytes from 8 consecutive lanes
+    const int ch = tid & 7;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int cl = (tid >> 3) + 64 * pass;
+        if (c0 + cl < cols && rb0 + ch < nrb)
+            *reinterpret_cast<uint4 *>(q + (c0 + cl) * (rows >> 1) + (rb0 + ch) * 16) = lds_q[ch][cl];
+    }
+    if (tid < CT_COLS && c0 + tid < cols) {
+        uint8_t *dst = s + (c0 + tid) * nrb + rb0;
+        if (s_vec8 && rb0 + CT_RB <= nrb) {
+            *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(&lds_s[tid][0]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < CT_RB; ++k)
+                if (rb0 + k < nrb) dst[k] = lds_s[tid][k];
+        }
+    }
+}
+
+template <int HAD>
+hipError_t launch_rows_h(const QuantArgs &a, hipStream_t st)
+{
+    const int64_t bpr = a.cols / 32, nblocks = a.rows * bpr;
+    const unsigned grid = (unsigned)((nblocks + 255) / 256);
+    const RngKey key = make_key(a.seed);
+    const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
+    const int dense = (a.ld == a.cols);
+    if (a.rounding == RND_RNE)
+        hipLaunchKernelGGL((quantize_rows_kernel<HAD, RND_RNE>), dim3(grid), dim3(256), 0, st, a.x, nblocks, bpr,
+                           a.ld, dense, sign_mask, key, a.q, a.s);
+    else
+        hipLaunchKernelGGL((quantize_rows_kernel<HAD, RND_SR>), dim3(grid), dim3(256), 0, st, a.x, nblocks, bpr,
+                           a.ld, dense, sign_mask, key, a.q, a.s);
+    return hipGetLastError();
+}
+
+template <int HAD>
+hipError_t launch_cols_h(const QuantArgs &a, hipStream_t st)
+{
+    const int64_t nrb = a.rows / 32;
+    // 1-D grid, column groups fastest: neighbouring workgroups read neighbouring memory
+    const uint32_t col_groups = (uint32_t)((a.cols + CT_COLS - 1) / CT_COLS);
+    dim3 grid((unsigned)(col_groups * ((nrb + CT_RB - 1) / CT_RB)));
+    const RngKey key = make_key(a.seed);
+    const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
+    const int s_vec8 = ((nrb % 8) == 0) && ((reinterpret_cast<uintptr_t>(a.s) % 8) == 0);
+    if (a.rounding == RND_RNE)
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols, a.ld,
+                           sign_mask, key, a.q, a.s, s_vec8, col_groups);
+    else
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR>), grid, dim3(512), 0, st, a.x, a.rows, a.cols, a.ld,
+                           sign_mask, key, a.q, a.s, s_vec8, col_groups);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st)
+{
+    switch (a.hadamard) {
+        case HAD_NONE: return launch_rows_h<HAD_NONE>(a, st);
+        case HAD_DET: return launch_rows_h<HAD_DET>(a, st);
+        case HAD_RANDSIGN: return launch_rows_h<HAD_RANDSIGN>(a, st);
+        default: return launch_rows_h<HAD_DET16>(a, st);
+    }
+}
+
+hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st)
+{
+    switch (a.hadamard) {
+        case HAD_NONE: return launch_cols_h<HAD_NONE>(a, st);
+        case HAD_DET: return launch_cols_h<HAD_DET>(a, st);
+        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN>(a, st);
+        default: return launch_cols_h<HAD_DET16>(a, st);
+    }
+}
+
+}  // namespace mxfp4

@@ -1,0 +1,114 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and every argument error is caught on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_09825_amd as mx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(mx.LIB_PATH):
+        from paper_2605_09825_amd.build import build
+        build()
+    return mx.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mxfp4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mxfp4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(L):
+    names = declared_symbols()
+    assert set(names) == set(mx.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings(L):
+    seen = set()
+    for code in range(7):
+        s = mx.status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert mx.status_string(99) == "unknown status"
+
+
+P = 0x10000  # a fake, 16-byte aligned, non-null device address: never dereferenced on the host
+
+
+def test_quantize_argument_errors(L):
+    q = L.mxfp4_quantize
+    assert q(P, 64, 64, 64, 2, 0, 0, 0, P, P, None) == mx.EINVAL          # axis
+    assert q(P, 64, 64, 64, 0, 9, 0, 0, P, P, None) == mx.EINVAL          # hadamard
+    assert q(P, 64, 64, 64, 0, 0, 2, 0, P, P, None) == mx.EINVAL          # rounding
+    assert q(None, 64, 64, 64, 0, 0, 0, 0, P, P, None) == mx.EINVAL
+    assert q(P, 64, 64, 64, 0, 0, 0, 0, None, P, None) == mx.EINVAL
+    assert q(P, 64, 64, 64, 0, 0, 0, 0, P, None, None) == mx.EINVAL
+    assert q(P, -1, 64, 64, 0, 0, 0, 0, P, P, None) == mx.ESHAPE
+    assert q(P, 64, 48, 48, 0, 0, 0, 0, P, P, None) == mx.ESHAPE          # cols % 32
+    assert q(P, 48, 64, 64, 1, 0, 0, 0, P, P, None) == mx.ESHAPE          # rows % 32 for AXIS_FIRST
+    assert q(P, 64, 63, 64, 1, 0, 0, 0, P, P, None) == mx.ESHAPE          # odd cols for AXIS_FIRST
+    assert q(P, 64, 64, 32, 0, 0, 0, 0, P, P, None) == mx.ESHAPE          # ld < cols
+    assert q(P + 2, 64, 64, 64, 0, 0, 0, 0, P, P, None) == mx.EALIGN
+    assert q(P, 64, 64, 64, 0, 0, 0, 0, P + 8, P, None) == mx.EALIGN
+    assert q(P, 64, 64, 68, 0, 0, 0, 0, P, P, None) == mx.EALIGN          # ld % 8
+    assert q(P, 64, 64, 65, 1, 0, 0, 0, P, P, None) == mx.EALIGN          # ld % 2 for AXIS_FIRST
+    assert q(P + 2, 64, 64, 64, 1, 0, 0, 0, P, P, None) == mx.EALIGN
+    assert q(None, 0, 64, 64, 0, 0, 0, 0, None, None, None) == mx.OK      # empty
+
+
+def test_gemm_argument_errors(L):
+    g = L.mxfp4_gemm
+    assert g(P, P, P, P, 16, 16, 32, P, 16, 5, 0, None) == mx.EINVAL      # dtype
+    assert g(P, P, P, P, 16, 16, 32, P, 16, mx.OUT_BF16, 1, None) == mx.EINVAL  # accumulate into bf16
+    assert g(P, P, P, P, 16, 16, 32, P, 16, mx.OUT_FP32, 2, None) == mx.EINVAL
+    assert g(P, P, P, P, 16, 16, 48, P, 16, 1, 0, None) == mx.ESHAPE      # C % 32
+    assert g(P, P, P, P, -1, 16, 32, P, 16, 1, 0, None) == mx.ESHAPE
+    assert g(P, P, P, P, 16, 16, 32, P, 8, 1, 0, None) == mx.ESHAPE       # ld < R_b
+    assert g(None, P, P, P, 16, 16, 32, P, 16, 1, 0, None) == mx.EINVAL
+    assert g(P, P, P, P, 16, 16, 32, None, 16, 1, 0, None) == mx.EINVAL
+    assert g(P + 4, P, P, P, 16, 16, 32, P, 16, 1, 0, None) == mx.EALIGN
+    assert g(P, P, P, P, 0, 16, 32, None, 16, 1, 0, None) == mx.OK        # empty
+
+
+def test_linear_argument_errors_and_workspace(L):
+    cfg = mx.make_cfg()
+    M, N, K = 64, 96, 128
+    need_f = mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, False)
+    need_b = mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, True)
+    assert need_f >= (M + N) * (K // 2 + K // 32)
+    assert need_b >= (M + K) * (N // 2 + N // 32) + (N + K) * (M // 2 + M // 32)
+    off = mx.mxfp4_linear_workspace_layout(M, N, K, True)
+    assert off == sorted(off) and all(o % 256 == 0 for o in off) and off[-1] + K * (M // 32) <= need_b
+    W = 0x100000
+    f, b = L.mxfp4_linear_fwd, L.mxfp4_linear_bwd
+    c = ctypes.byref(cfg)
+    assert f(P, P, P, M, N, K, None, W, need_f, None) == mx.EINVAL
+    assert f(P, P, P, M, N, 100, c, W, need_f, None) == mx.ESHAPE
+    assert f(P, P, P, 0, N, K, c, W, need_f, None) == mx.ESHAPE
+    assert f(None, P, P, M, N, K, c, W, need_f, None) == mx.EINVAL
+    assert f(P, P, P, M, N, K, c, W, need_f - 1, None) == mx.EWORKSPACE
+    assert f(P, P, P, M, N, K, c, W + 16, need_f, None) == mx.EALIGN
+    bad = mx.make_cfg(dw_dtype=mx.OUT_BF16, dw_accumulate=True)
+    assert f(P, P, P, M, N, K, ctypes.byref(bad), W, need_f, None) == mx.EINVAL
+    assert b(P, P, P, P, P, M, N, K, c, W, need_b - 1, None) == mx.EWORKSPACE
+    assert b(P, P, P, P, P, M, 100, K, c, W, need_b, None) == mx.ESHAPE   # Dgrad needs N % 32
+    assert b(P, P, P, None, P, 48, N, K, c, W, need_b, None) == mx.ESHAPE  # Wgrad needs M % 32
+    assert b(P, None, P, P, P, M, N, K, c, W, need_b, None) == mx.EINVAL  # x needed for dW
+    assert b(P, P, None, P, P, M, N, K, c, W, need_b, None) == mx.EINVAL  # w needed for dX
+    assert b(P, P, P, None, None, M, N, K, c, W, need_b, None) == mx.OK   # nothing asked
+
+
+def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
+    monkeypatch.setattr(mx, "_lib", None)
+    monkeypatch.setattr(mx, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        mx.lib()

@@ -1,0 +1,103 @@
+"""GPU parity of the fused linear calls against the oracle's composition of quantise and GEMM,
+stage by stage (App. C.1 Fprop, C.2 Dgrad, C.3 Wgrad)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_09825_amd as mx
+from paper_2605_09825_amd import synth
+from test_gpu_gemm import assert_close, sample_positions
+
+pytestmark = pytest.mark.gpu
+
+
+def ws_slices(ws, M, N, K, bwd):
+    off = mx.mxfp4_linear_workspace_layout(M, N, K, bwd)
+    w = ws.cpu().numpy()
+    if not bwd:
+        dims = [(M, K), (N, K)]
+    else:
+        dims = [(M, N), (K, N), (N, M), (K, M)]
+    out = []
+    for k, (R, C) in enumerate(dims):
+        q = w[off[2 * k]: off[2 * k] + R * C // 2].reshape(R, C // 2)
+        s = w[off[2 * k + 1]: off[2 * k + 1] + R * C // 32].reshape(R, C // 32)
+        out.append((q, s))
+    return out
+
+
+@pytest.mark.parametrize("had,rnd", [(mx.HAD_NONE, mx.RNE), (mx.HAD_DET, mx.RNE), (mx.HAD_RANDSIGN, mx.RNE),
+                                     (mx.HAD_NONE, mx.SR), (mx.HAD_DET16, mx.RNE)])
+@pytest.mark.parametrize("shape", [(256, 512, 512), (96, 160, 224)])
+def test_linear_fwd_and_bwd(shape, had, rnd):
+    M, N, K = shape
+    seed = 77
+    x = synth.normal(M, K, 1.0, 1, synth.STREAM_X)
+    w = synth.normal(N, K, 0.02, 1, synth.STREAM_W)
+    dy = synth.normal(M, N, 1e-3, 1, synth.STREAM_DY)
+    cfg = mx.make_cfg(had, rnd, seed, y_dtype=mx.OUT_FP32, dx_dtype=mx.OUT_FP32, dw_dtype=mx.OUT_FP32)
+    xg, wg, dyg = x.to("cuda:0"), w.to("cuda:0"), dy.to("cuda:0")
+    y, ws_f = mx.mxfp4_linear_fwd(xg, wg, cfg)
+    dx, dw, ws_b = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg)
+    torch.cuda.synchronize()
+    xb, wb, dyb = synth.as_u16(x), synth.as_u16(w), synth.as_u16(dy)
+
+    # operands left in the workspace: byte parity with the oracle's quantiser
+    ops_f = oracle.linear_fwd_operands(xb, wb, had, rnd, seed)
+    for (q, s), (qo, so) in zip(ws_slices(ws_f, M, N, K, False), ops_f):
+        assert np.array_equal(q, qo) and np.array_equal(s, so)
+    ops_b = list(oracle.linear_dgrad_operands(dyb, wb, had, rnd, seed)) + \
+        list(oracle.linear_wgrad_operands(dyb, xb, had, rnd, seed))
+    for (q, s), (qo, so) in zip(ws_slices(ws_b, M, N, K, True), ops_b):
+        assert np.array_equal(q, qo) and np.array_equal(s, so)
+
+    yo, ya = oracle.linear_fwd(xb, wb, had, rnd, seed)
+    (dxo, dxa), (dwo, dwa) = oracle.linear_bwd(dyb, xb, wb, had, rnd, seed)
+    assert y.shape == (M, N) and dx.shape == (M, K) and dw.shape == (N, K)
+    assert_close(y.cpu().numpy(), yo, ya)
+    assert_close(dx.cpu().numpy(), dxo, dxa)
+    assert_close(dw.cpu().numpy(), dwo, dwa)
+
+
+def test_bwd_skips_and_accumulates():
+    M, N, K = 64, 96, 128
+    x = synth.normal(M, K, 1.0, 2, synth.STREAM_X).to("cuda:0")
+    w = synth.normal(N, K, 0.02, 2, synth.STREAM_W).to("cuda:0")
+    dy = synth.normal(M, N, 1e-3, 2, synth.STREAM_DY).to("cuda:0")
+    cfg = mx.make_cfg(mx.HAD_DET, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32)
+    dx, dw, _ = mx.mxfp4_linear_bwd(dy, x, w, cfg)
+    dx_only, none_dw, _ = mx.mxfp4_linear_bwd(dy, None, w, cfg, need_dw=False)
+    none_dx, dw_only, _ = mx.mxfp4_linear_bwd(dy, x, None, cfg, need_dx=False)
+    torch.cuda.synchronize()
+    assert none_dw is None and none_dx is None
+    assert torch.equal(dx, dx_only) and torch.equal(dw, dw_only)
+    acc = mx.make_cfg(mx.HAD_DET, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32, dw_accumulate=True)
+    dw2 = dw.clone()
+    mx.mxfp4_linear_bwd(dy, x, w, acc, dw=dw2, need_dx=False)
+    torch.cuda.synchronize()
+    assert torch.allclose(dw2, 2 * dw, rtol=1e-6, atol=0)
+
+
+def test_config2_all_three_stages_sampled():
+    # Llama-3.1-8B fused QKV: M=8192, K=4096, N=6144, deterministic Hadamard, RNE
+    M, N, K = 8192, 6144, 4096
+    x = synth.normal(M, K, 1.0, 0, synth.STREAM_X)
+    w = synth.normal(N, K, 0.02, 0, synth.STREAM_W)
+    dy = synth.normal(M, N, 1e-3, 0, synth.STREAM_DY)
+    cfg = mx.make_cfg(mx.HAD_DET, y_dtype=mx.OUT_FP32, dx_dtype=mx.OUT_FP32, dw_dtype=mx.OUT_FP32)
+    xg, wg, dyg = x.to("cuda:0"), w.to("cuda:0"), dy.to("cuda:0")
+    y, _ = mx.mxfp4_linear_fwd(xg, wg, cfg)
+    dx, dw, _ = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg)
+    torch.cuda.synchronize()
+    xb, wb, dyb = synth.as_u16(x), synth.as_u16(w), synth.as_u16(dy)
+    rng = np.random.default_rng(1)
+    stages = [
+        (y, oracle.linear_fwd_operands(xb, wb, mx.HAD_DET)),
+        (dx, oracle.linear_dgrad_operands(dyb, wb, mx.HAD_DET)),
+        (dw, oracle.linear_wgrad_operands(dyb, xb, mx.HAD_DET)),
+    ]
+    for out, ((aq, as_), (bq, bs)) in stages:
+        ii, jj = sample_positions(rng, out.shape[0], out.shape[1], n_rows=2, n_cols=2, n_tiles=16)
+        want, absum = oracle.gemm_at(aq, as_, bq, bs, ii, jj)
+        assert_close(out.cpu().numpy()[ii, jj], want, absum)

@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the MXFP4 linear-layer hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic input: for the
+Llama-3.1-8B fused QKV projection (M=8192 tokens, K=4096, N=6144) the three training GEMMs
+Fprop, Dgrad and Wgrad, each preceded by the deterministic 32-point Hadamard rotation and the
+MXFP4 quantisation of both operands (6 quantiser launches + 3 GEMM launches per step).
+Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = 3 * 2*M*N*K flop / step time, i.e. GEMM TFLOP/s including the
+rotation and quantisation time.  `roofline` describes the dominant kernel (the FP4 GEMM)
+against the dense MXFP4 MFMA peak; `quantizer` the fused rotate+quantise kernels against peak
+HBM bandwidth (measured on a rotation of buffers larger than the 256 MB last-level cache);
+`cpu_baseline` the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+M, K, N = 8192, 4096, 6144
+PEAK_FP4_TFLOPS = 10100.0  # MI355X dense MXFP4 MFMA peak
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
+BYTES_PER_ELEM = 2.0 + 0.5 + 1.0 / 32.0  # bf16 read + packed codes + scale byte per element
+
+# HBM traffic per GEMM launch measured with `rocprofv3 --pmc` (see profiles/); None until measured
+GEMM_TRAFFIC_BYTES = None
+
+
+def event_time_ms(fn, iters, torch):
+    """Average duration of fn() in ms measured with events on the current stream."""
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2605_09825_amd as mx
+    from paper_2605_09825_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    mx.lib()  # fail loudly now if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    x_cpu = synth.normal(M, K, 1.0, 0, synth.STREAM_X)
+    w_cpu = synth.normal(N, K, 0.02, 0, synth.STREAM_W)
+    dy_cpu = synth.normal(M, N, 1e-3, 0, synth.STREAM_DY)
+    x, w, dy = x_cpu.to(dev), w_cpu.to(dev), dy_cpu.to(dev)
+
+    cfg = mx.make_cfg(mx.HAD_DET, mx.RNE, 0, y_dtype=mx.OUT_BF16, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32)
+    ws_f = torch.empty(mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, False), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, True), dtype=torch.uint8, device=dev)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    dw = torch.empty((N, K), dtype=torch.float32, device=dev)
+
+    def step():
+        mx.mxfp4_linear_fwd(x, w, cfg, y=y, workspace=ws_f)
+        mx.mxfp4_linear_bwd(dy, x, w, cfg, dx=dx, dw=dw, workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flop_step = 3 * 2.0 * M * N * K
+    tflops_incl = flop_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel durations, live, with events on the launch stream -------------------------
+    off_f = mx.mxfp4_linear_workspace_layout(M, N, K, False)
+    off_b = mx.mxfp4_linear_workspace_layout(M, N, K, True)
+
+    def view(ws, off, R, C, k):
+        q = ws[off[2 * k]: off[2 * k] + R * C // 2].view(R, C // 2)
+        s = ws[off[2 * k + 1]: off[2 * k + 1] + R * C // 32].view(R, C // 32)
+        return q, s
+
+    xq, xs = view(ws_f, off_f, M, K, 0)
+    wq, wsc = view(ws_f, off_f, N, K, 1)
+    gq, gs = view(ws_b, off_b, M, N, 0)
+    wtq, wts = view(ws_b, off_b, K, N, 1)
+    gtq, gts = view(ws_b, off_b, N, M, 2)
+    xtq, xts = view(ws_b, off_b, K, M, 3)
+    iters = max(5, args.steps)
+    t_fprop = event_time_ms(lambda: mx.mxfp4_gemm(xq, xs, wq, wsc, out=y, out_dtype=mx.OUT_BF16), iters, torch)
+    t_dgrad = event_time_ms(lambda: mx.mxfp4_gemm(gq, gs, wtq, wts, out=dx, out_dtype=mx.OUT_BF16), iters, torch)
+    t_wgrad = event_time_ms(lambda: mx.mxfp4_gemm(gtq, gts, xtq, xts, out=dw, out_dtype=mx.OUT_FP32), iters, torch)
+    t_gemm = (t_fprop + t_dgrad + t_wgrad) / 3.0
+    gemm_tflops = 2.0 * M * N * K / (t_gemm * 1e-3) / 1e12
+
+    def q_rows(t, q, s):
+        mx.mxfp4_quantize(t, mx.AXIS_LAST, mx.HAD_DET, mx.RNE, 0, q=q, s=s)
+
+    def q_cols(t, q, s):
+        mx.mxfp4_quantize(t, mx.AXIS_FIRST, mx.HAD_DET, mx.RNE, 0, q=q, s=s)
+
+    t_q = {
+        "x_rows": event_time_ms(lambda: q_rows(x, xq, xs), iters, torch),
+        "w_rows": event_time_ms(lambda: q_rows(w, wq, wsc), iters, torch),
+        "dy_rows": event_time_ms(lambda: q_rows(dy, gq, gs), iters, torch),
+        "w_cols": event_time_ms(lambda: q_cols(w, wtq, wts), iters, torch),
+        "dy_cols": event_time_ms(lambda: q_cols(dy, gtq, gts), iters, torch),
+        "x_cols": event_time_ms(lambda: q_cols(x, xtq, xts), iters, torch),
+    }
+    elems = {"x_rows": M * K, "w_rows": N * K, "dy_rows": M * N, "w_cols": N * K, "dy_cols": M * N, "x_cols": M * K}
+    t_quant_total = sum(t_q.values())
+
+    # HBM-resident rate: rotate over 10 distinct X-sized inputs (640 MiB > the 256 MB last-level cache)
+    rot = [x] + [torch.empty_like(x).copy_(x) for _ in range(9)]
+    state = {"i": 0}
+
+    def q_rot(fn):
+        def run():
+            fn(rot[state["i"] % len(rot)], xq if fn is q_rows else xtq, xs if fn is q_rows else xts)
+            state["i"] += 1
+        return run
+
+    n_rot = 2 * len(rot)
+    q_rot(q_rows)()
+    q_rot(q_cols)()
+    t_rows_cold = event_time_ms(q_rot(q_rows), n_rot, torch)
+    t_cols_cold = event_time_ms(q_rot(q_cols), n_rot, torch)
+    del rot
+    gbs = lambda n_el, ms: n_el * BYTES_PER_ELEM / (ms * 1e-3) / 1e9
+    quant_rows_gbs, quant_cols_gbs = gbs(M * K, t_rows_cold), gbs(M * K, t_cols_cold)
+
+    out = {
+        "metric": "mxfp4_linear_gemm_tflops_incl_hadamard_quantize",
+        "value": round(tflops_incl, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp4",
+        "data": "synthetic",
+        "config": {
+            "workload": "Llama-3.1-8B fused QKV linear, Fprop+Dgrad+Wgrad, M=8192 K=4096 N=6144, "
+                        "deterministic H32 + MXFP4 RNE on both operands of each GEMM; y,dx bf16, dw fp32",
+            "M": M, "K": K, "N": N, "launches_per_step": 9,
+        },
+        "pct_of_fp4_peak_incl_quant": round(100.0 * tflops_incl / PEAK_FP4_TFLOPS, 2),
+        "roofline": {
+            "kernel": "mxfp4 gemm (mean of fprop, dgrad, wgrad launches)",
+            "bound": "mfma",
+            "achieved": round(gemm_tflops, 2),
+            "peak": PEAK_FP4_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
+            "traffic": GEMM_TRAFFIC_BYTES,
+            "launch_ms": {"fprop": round(t_fprop, 4), "dgrad": round(t_dgrad, 4), "wgrad": round(t_wgrad, 4)},
+        },
+        "quantizer": {
+            "bound": "hbm",
+            "unit": "GB/s",
+            "peak": PEAK_HBM_GBS,
+            "bytes_per_element": BYTES_PER_ELEM,
+            "rows_hbm_resident": {"achieved": round(quant_rows_gbs, 1), "frac": round(quant_rows_gbs / PEAK_HBM_GBS, 4),
+                                  "launch_ms": round(t_rows_cold, 4)},
+            "cols_hbm_resident": {"achieved": round(quant_cols_gbs, 1), "frac": round(quant_cols_gbs / PEAK_HBM_GBS, 4),
+                                  "launch_ms": round(t_cols_cold, 4)},
+            "in_step_ms": {k: round(v, 4) for k, v in t_q.items()},
+            "in_step_gbs_cache_warm": {k: round(gbs(elems[k], v), 1) for k, v in t_q.items()},
+        },
+        "breakdown_ms": {"gemm_total": round(3 * t_gemm, 4), "quantize_total": round(t_quant_total, 4)},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        Ms = 512  # the first 512 of the 8192 tokens; all of N and K; all three stages
+        xb, wb, dyb = synth.as_u16(x_cpu[:Ms]), synth.as_u16(w_cpu), synth.as_u16(dy_cpu[:Ms])
+        c0 = time.perf_counter()
+        oracle.linear_fwd(xb, wb, oracle.HAD_DET)
+        oracle.linear_bwd(dyb, xb, wb, oracle.HAD_DET)
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {
+            "value": round(3 * 2.0 * Ms * N * K / (c1 - c0) / 1e12, 6),
+            "unit": "TFLOP/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"first {Ms} of {M} tokens, full N and K, Fprop+Dgrad+Wgrad with rotation and "
+                      f"quantisation; {round(c1 - c0, 2)} s",
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -34,10 +34,21 @@ __device__ __forceinline__ v4f mfma_fp4(v4i first, v4i second, v4f acc, int scal
 
 __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    // round to nearest even on the upper 16 bits; NaN keeps a quiet NaN (branch-free)
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const uint32_t nan = (u >> 16) | 0x40u;
+    return (uint16_t)(((u & 0x7FFFFFFFu) > 0x7F800000u) ? nan : rounded);
+}
+
+// two floats -> two bf16 in one dword (first in the low half), round to nearest even: one
+// V_CVT_PK_BF16_F32
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // ---- any-shape kernel --------------------------------------------------------------------
@@ -123,20 +134,35 @@ __global__ __launch_bounds__(256) void gemm_any_kernel(const uint8_t *__restrict
 // block's scale byte; the result holds, in register e of lane l, D[8*(e/4) + 4*(l/32) + e%4][l%32].
 //
 // Data path: packed codes go global -> LDS with the direct-to-LDS loads (no registers), one
-// instruction per 8 rows x 128 bytes (whole cache lines).  A wave's 64 lanes land at
-// consecutive 16-byte slots, so the lane -> (row, 16-byte chunk) choice on the global side fixes
-// the LDS layout; chunk c of row r of an 8-row group g sits at slot r*8 + (c ^ r ^ (g&1)),
-// which makes every 16-lane quarter of the later 16-byte fragment reads hit all 64 banks once.
-// Scale bytes follow the same way (8 per row and stage) and are regrouped with one byte
-// permute so that the instruction's byte selector picks the K-step.
+// instruction per 8 rows x 128 bytes (whole cache lines: the memory pipeline's cost is per
+// request, about 0.45 lines per clock and CU, so partial lines are ruinous).  A wave's 64 lanes
+// land at consecutive 16-byte LDS slots, so the lane -> (row, 16-byte chunk) choice on the
+// global side fixes the LDS layout; chunk c of row r of an 8-row group g sits at slot
+// r*8 + (c ^ r ^ (g&1)), which makes every 16-lane quarter of the later 16-byte fragment reads
+// hit all 64 banks once.
+// Scale bytes: one row has 8 per stage, far too little for a request of its own, so they
+// come in batches of 4 stages (32 bytes per row, two lanes per row), double-buffered; the
+// four load instructions of the next batch are spread over the four stages of the current one.
+// A byte permute puts the 4 scale bytes a lane needs in one stage into one register, from which
+// the instruction's byte selector picks the K-step.
 // Two LDS stage buffers; fragments are double-buffered in registers across the 4 K-steps.
+// Epilogue: every wave transposes its sub-tile through its own LDS slice so that global
+// stores are whole 256- or 512-byte row segments.
 constexpr int TILE = 256;                       // output tile edge
 constexpr int STAGE_K = 256;                    // K elements per stage = 128 bytes per row
 constexpr int OP_BYTES = TILE * STAGE_K / 2;    // 32 KiB per operand and stage
-constexpr int SC_BYTES = TILE * 8;              // 2 KiB of scale bytes per operand and stage
-constexpr int OFF_A = 0, OFF_B = OP_BYTES, OFF_SA = 2 * OP_BYTES, OFF_SB = 2 * OP_BYTES + SC_BYTES;
-constexpr int STAGE_BYTES = 2 * OP_BYTES + 2 * SC_BYTES;  // 69632
+constexpr int STAGE_BYTES = 2 * OP_BYTES;       // 64 KiB
+constexpr int OFF_A = 0, OFF_B = OP_BYTES;
+constexpr int SCALE_BATCH = 4;                  // stages per scale batch
+constexpr int SC_OP_BYTES = TILE * 8 * SCALE_BATCH;  // 8 KiB per operand and batch
+constexpr int SC_BUF_BYTES = 2 * SC_OP_BYTES;        // 16 KiB
+constexpr int OFF_SC = 2 * STAGE_BYTES;              // scale buffers behind the two stage buffers
+constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * SC_BUF_BYTES;  // 163840 = all of the CU's LDS
 constexpr int GROUP_M = 4;                      // tile rows per rasterisation group
+constexpr int PREFETCH_AHEAD = 4;               // stages between the L2 prefetch and the stage in use
+constexpr int EPI_PITCH_BF16 = 256 + 8;         // bytes per staged row of 128 bf16 (+ bank skew)
+constexpr int EPI_PITCH_F32 = 512 + 16;         // bytes per staged row of 128 fp32 (+ bank skew)
+constexpr int EPI_WAVE_BYTES = 33792;           // 128 x 264 = 64 x 528
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
@@ -144,12 +170,6 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const ui
 {
     // each lane: 16 bytes from sbase + voff to LDS[lds_addr + 16*lane]
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t" ::"s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory");
-}
-__device__ __forceinline__ void dma4(uint32_t lds_addr, uint32_t voff, const uint8_t *sbase)
-{
-    // each lane: 4 bytes from sbase + voff to LDS[lds_addr + 4*lane]
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2\n\t" ::"s"(lds_addr), "v"(voff), "s"(sbase)
                  : "memory");
 }
 
@@ -161,7 +181,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
                                                            void *__restrict__ out, int64_t ld, int tiles_m,
                                                            int tiles_n)
 {
-    __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -190,27 +210,59 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
     const int drr = lane >> 3, dcc = lane & 7;
     const uint32_t dvoff0 = (uint32_t)(drr * rowbytes) + (uint32_t)((dcc ^ drr) << 4);        // even 8-row groups
     const uint32_t dvoff1 = (uint32_t)(drr * rowbytes) + (uint32_t)((dcc ^ drr ^ 1) << 4);    // odd ones
-    const uint32_t svoff = (uint32_t)(lane * nkb);
+    const uint32_t svoff = (uint32_t)((lane >> 1) * nkb) + (uint32_t)((lane & 1) << 4);
     const uint8_t *a_rows = aq + (m0 + wave * 64) * rowbytes;  // this wave loads rows wave*64 .. +63 of each tile
     const uint8_t *b_rows = bq + (n0 + wave * 64) * rowbytes;
     const uint8_t *as_rows = as + (m0 + wave * 64) * nkb;
     const uint8_t *bs_rows = bs + (n0 + wave * 64) * nkb;
 
-    auto issue_stage = [&](int s, int buf) {
+    // load n (0..15) of stage s for this wave: even n -> A, odd n -> B; 8-row group n/2 of the wave's 64 rows
+    auto issue_load = [&](int s, int buf, int n) {
         const uint32_t base = lds0 + buf * STAGE_BYTES;
         const int64_t koff = (int64_t)s * (STAGE_K / 2);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const uint32_t dst = (uint32_t)((wave * 8 + t) * 1024);
-            const uint32_t vo = (t & 1) ? dvoff1 : dvoff0;
-            dma16(base + OFF_A + dst, vo, a_rows + t * 8 * rowbytes + koff);
-            dma16(base + OFF_B + dst, vo, b_rows + t * 8 * rowbytes + koff);
-        }
-#pragma unroll
-        for (int d = 0; d < 2; ++d) {
-            dma4(base + OFF_SA + d * 1024 + wave * 256, svoff, as_rows + s * 8 + d * 4);
-            dma4(base + OFF_SB + d * 1024 + wave * 256, svoff, bs_rows + s * 8 + d * 4);
-        }
+        const int g = n >> 1;
+        const uint32_t dst = (uint32_t)((wave * 8 + g) * 1024);
+        const uint32_t vo = (g & 1) ? dvoff1 : dvoff0;
+        if (n & 1)
+            dma16(base + OFF_B + dst, vo, b_rows + g * 8 * rowbytes + koff);
+        else
+            dma16(base + OFF_A + dst, vo, a_rows + g * 8 * rowbytes + koff);
+    };
+    // Scale batch b holds the 32 scale bytes per row of stages first(b) .. first(b)+3, where
+    // first(b) = min(4b, nstages-4): the last batch is pulled back so that it never reads past a
+    // row's end (batches past the end of K just repeat the last one into the idle buffer).
+    auto batch_first = [&](int b) { return (4 * b < nstages - 4) ? 4 * b : nstages - 4; };
+    // instruction j (0..3) of batch b for this wave: j>>1 = operand, j&1 = which 32 of its 64 rows
+    auto issue_scales = [&](int b, int j) {
+        const uint8_t *rows = (j >> 1) ? bs_rows : as_rows;
+        const uint32_t dst = lds0 + OFF_SC + (b & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES +
+                             (wave * 64 + (j & 1) * 32) * 32;
+        dma16(dst, svoff, rows + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * 8);
+    };
+
+    // ---- L2 prefetch ---------------------------------------------------------------------------
+    // The operands do not fit the XCD's 4 MB L2, so each stage's lines come from the last-level
+    // cache or HBM with a latency of more than a stage.  The tiles running together on an XCD
+    // (4 tile rows x 8 tile columns, see the rasterisation above) share their A and B panels, so
+    // each pulls a 1/8 slice of its A panel and a 1/4 slice of its B panel of the stage
+    // PREFETCH_AHEAD ahead into L2 with ordinary loads whose results are never used (3 loads per
+    // wave and stage); the direct-to-LDS loads of all of them then hit in L2.  Purely a hint: a
+    // slice nobody fetched is just a slower load.  The destination registers are pinned for the
+    // whole loop ("+v") because the data arrives long after the instruction has issued.
+    const uint32_t pvoff = (uint32_t)((lane >> 3) * rowbytes) + (uint32_t)((lane & 7) << 4);
+    const uint8_t *a_pf = aq + (m0 + 32 * (tn & 7) + 8 * wave) * rowbytes;
+    const uint8_t *b_pf = bq + (n0 + 64 * (tm & 3) + 16 * wave) * rowbytes;
+    v4i pf0 = {0, 0, 0, 0}, pf1 = pf0, pf2 = pf0;
+    auto prefetch = [&](int s, int which) {
+        const int sp = (s + PREFETCH_AHEAD < nstages) ? s + PREFETCH_AHEAD : nstages - 1;
+        const int64_t koff = (int64_t)sp * (STAGE_K / 2);
+        if (which == 0)
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(pf0) : "v"(pvoff), "s"(a_pf + koff) : "memory");
+        else if (which == 1)
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(pf1) : "v"(pvoff), "s"(b_pf + koff) : "memory");
+        else
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(pf2) : "v"(pvoff), "s"(b_pf + 8 * rowbytes + koff)
+                         : "memory");
     };
 
     // ---- fragment reads: per-lane offsets ---------------------------------------------------
@@ -221,7 +273,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) foff[kk] = fl0 + (uint32_t)((((kk << 1) | fh) ^ fm) << 4);
     const uint32_t a_frag0 = OFF_A + wm * 16 * 1024, b_frag0 = OFF_B + wn * 16 * 1024;
-    const uint32_t sa_frag0 = OFF_SA + (wm * 128 + fr) * 4, sb_frag0 = OFF_SB + (wn * 128 + fr) * 4;
+    const uint32_t sa_frag0 = OFF_SC + (wm * 128 + fr) * 32, sb_frag0 = OFF_SC + SC_OP_BYTES + (wn * 128 + fr) * 32;
     const uint32_t perm_sel = fh ? 0x07050301u : 0x06040200u;
 
     v4i fa[2][4], fb[2][4];
@@ -233,16 +285,15 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
             fb[set][i] = *reinterpret_cast<const v4i *>(p + b_frag0 + i * 4096);
         }
     };
-    auto read_scales = [&](int buf, int (&sa)[4], int (&sb)[4]) {
-        const uint8_t *p = smem + buf * STAGE_BYTES;
+    auto read_scales = [&](int s, int (&sa)[4], int (&sb)[4]) {
+        const int b = s >> 2;
+        const uint8_t *p = smem + (b & 1) * SC_BUF_BYTES + (s - batch_first(b)) * 8;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t a0 = *reinterpret_cast<const uint32_t *>(p + sa_frag0 + i * 128);
-            const uint32_t a1 = *reinterpret_cast<const uint32_t *>(p + sa_frag0 + 1024 + i * 128);
-            const uint32_t b0 = *reinterpret_cast<const uint32_t *>(p + sb_frag0 + i * 128);
-            const uint32_t b1 = *reinterpret_cast<const uint32_t *>(p + sb_frag0 + 1024 + i * 128);
-            sa[i] = (int)__builtin_amdgcn_perm(a1, a0, perm_sel);  // bytes: K blocks fh, 2+fh, 4+fh, 6+fh
-            sb[i] = (int)__builtin_amdgcn_perm(b1, b0, perm_sel);
+            const uint2 a = *reinterpret_cast<const uint2 *>(p + sa_frag0 + i * 1024);
+            const uint2 bb = *reinterpret_cast<const uint2 *>(p + sb_frag0 + i * 1024);
+            sa[i] = (int)__builtin_amdgcn_perm(a.y, a.x, perm_sel);  // bytes: K blocks fh, 2+fh, 4+fh, 6+fh
+            sb[i] = (int)__builtin_amdgcn_perm(bb.y, bb.x, perm_sel);
         }
     };
 
@@ -254,90 +305,169 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#define MXFP4_MMA_STEP(SET, KK, SA, SB)                                                                        \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) _Pragma("unroll") for (int j = 0; j < 4; ++j)                \
-    {                                                                                                          \
-        v8i fb8 = {fb[SET][j].x, fb[SET][j].y, fb[SET][j].z, fb[SET][j].w, 0, 0, 0, 0};                        \
-        v8i fa8 = {fa[SET][i].x, fa[SET][i].y, fa[SET][i].z, fa[SET][i].w, 0, 0, 0, 0};                        \
-        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8, fa8, acc[i][j], 4, 4, KK, SB[j], KK,  \
-                                                                    SA[i]);                                    \
+    // One matrix instruction: tile (n/4, n%4) of the wave's 4 x 4, fragments from register set SET,
+    // K-step KK selects the scale byte.
+#define MXFP4_MMA(SET, KK, N)                                                                                   \
+    {                                                                                                           \
+        constexpr int i_ = (N) >> 2, j_ = (N) & 3;                                                              \
+        v8i fb8 = {fb[SET][j_].x, fb[SET][j_].y, fb[SET][j_].z, fb[SET][j_].w, 0, 0, 0, 0};                     \
+        v8i fa8 = {fa[SET][i_].x, fa[SET][i_].y, fa[SET][i_].z, fa[SET][i_].w, 0, 0, 0, 0};                     \
+        acc[i_][j_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8, fa8, acc[i_][j_], 4, 4, KK,          \
+                                                                      sb_cur[j_], KK, sa_cur[i_]);              \
     }
 
-    int sa_cur[4], sb_cur[4], sa_nxt[4], sb_nxt[4];
-    issue_stage(0, 0);
-    if (nstages > 1) issue_stage(1, 1);
+    int sa_cur[4], sb_cur[4];
+    // prologue: all of stage 0, the first 8 loads of stage 1, scale batch 0 and the first load of batch 1
+#pragma unroll
+    for (int n = 0; n < 16; ++n) issue_load(0, 0, n);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) issue_load(1, 1, n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) issue_scales(0, j);
+    issue_scales(1, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     read_frags(0, 0, 0);
     read_scales(0, sa_cur, sb_cur);
 
-    // One stage.  The loop body must stay one basic block (no data-dependent branches inside),
-    // otherwise the matrix instructions get sunk behind the branches and stop overlapping the
-    // fragment fetches; so the last two stages, which issue fewer loads, are peeled below.
+    // One fragment fetch (f = 0..7: A0,B0,A1,B1,...) of K-step kk of buffer buf into register set `set`.
+    auto read_one = [&](int buf, int kk, int set, int f) {
+        const uint8_t *p = smem + buf * STAGE_BYTES + foff[kk] + (f >> 1) * 4096;
+        if (f & 1)
+            fb[set][f >> 1] = *reinterpret_cast<const v4i *>(p + b_frag0);
+        else
+            fa[set][f >> 1] = *reinterpret_cast<const v4i *>(p + a_frag0);
+    };
+    uint2 sraw[8];
+    auto read_scale_one = [&](int s, int f) {  // f = 0..7: A0,B0,A1,B1,...
+        const int b = s >> 2;
+        const uint8_t *p = smem + (b & 1) * SC_BUF_BYTES + (s - batch_first(b)) * 8 + (f >> 1) * 1024;
+        sraw[f] = *reinterpret_cast<const uint2 *>(p + ((f & 1) ? sb_frag0 : sa_frag0));
+    };
+
+    // One stage = 4 K-steps of 16 matrix instructions.  Everything else is threaded between them,
+    // one item per matrix instruction, and pinned there with scheduling barriers: with a single
+    // wave per SIMD any stall of the wave (a burst of loads filling the memory pipeline's queue,
+    // a late fragment) idles the matrix unit, so loads are issued a few at a time.
+    //   K-step 0: fragments of K-step 1; second half of the next stage's direct-to-LDS loads
+    //   K-step 1: fragments of K-step 2           K-step 2: fragments of K-step 3
+    //   barrier (this stage's buffer is free, the next stage has landed)
+    //   K-step 3: fragments + scales of the next stage's K-step 0; first half of the loads of
+    //             the stage after next, into the buffer just freed; one scale load
+    // The loop body must stay one basic block (no data-dependent branches), or the matrix
+    // instructions get sunk behind the branches; the last two stages are peeled instead.
+#define MXFP4_PIN() __builtin_amdgcn_sched_barrier(0);
     auto stage = [&](int s, auto refill, auto has_next) {
         const int buf = s & 1;
-        // each K-step: fetch the next step's fragments into the other register set, then the 16
-        // matrix instructions of this step; the scheduling barriers keep the compiler from
-        // regrouping all fetches ahead of all matrix instructions
-        read_frags(buf, 1, 1);
-        MXFP4_MMA_STEP(0, 0, sa_cur, sb_cur)
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(buf, 2, 0);
-        MXFP4_MMA_STEP(1, 1, sa_cur, sb_cur)
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(buf, 3, 1);
-        MXFP4_MMA_STEP(0, 2, sa_cur, sb_cur)
-        __builtin_amdgcn_sched_barrier(0);
+        constexpr bool kRefill = decltype(refill)::value, kNext = decltype(has_next)::value;
+#define MXFP4_K0(N)                                                        \
+        if ((N) < 8) read_one(buf, 1, 1, (N));                             \
+        if (kNext && ((N) & 1)) issue_load(s + 1, buf ^ 1, 8 + ((N) >> 1)); \
+        MXFP4_MMA(0, 0, N) MXFP4_PIN()
+        MXFP4_K0(0) MXFP4_K0(1) MXFP4_K0(2) MXFP4_K0(3) MXFP4_K0(4) MXFP4_K0(5) MXFP4_K0(6) MXFP4_K0(7)
+        MXFP4_K0(8) MXFP4_K0(9) MXFP4_K0(10) MXFP4_K0(11) MXFP4_K0(12) MXFP4_K0(13) MXFP4_K0(14) MXFP4_K0(15)
+#undef MXFP4_K0
+#define MXFP4_K1(N)                                                        \
+        if ((N) < 8) read_one(buf, 2, 0, (N));                             \
+        if (kRefill && ((N) == 9 || (N) == 11 || (N) == 13)) prefetch(s, ((N) - 9) >> 1); \
+        MXFP4_MMA(1, 1, N) MXFP4_PIN()
+        MXFP4_K1(0) MXFP4_K1(1) MXFP4_K1(2) MXFP4_K1(3) MXFP4_K1(4) MXFP4_K1(5) MXFP4_K1(6) MXFP4_K1(7)
+        MXFP4_K1(8) MXFP4_K1(9) MXFP4_K1(10) MXFP4_K1(11) MXFP4_K1(12) MXFP4_K1(13) MXFP4_K1(14) MXFP4_K1(15)
+#undef MXFP4_K1
+#define MXFP4_K2(N)                                                        \
+        if ((N) < 8) read_one(buf, 3, 1, (N));                             \
+        MXFP4_MMA(0, 2, N) MXFP4_PIN()
+        MXFP4_K2(0) MXFP4_K2(1) MXFP4_K2(2) MXFP4_K2(3) MXFP4_K2(4) MXFP4_K2(5) MXFP4_K2(6) MXFP4_K2(7)
+        MXFP4_K2(8) MXFP4_K2(9) MXFP4_K2(10) MXFP4_K2(11) MXFP4_K2(12) MXFP4_K2(13) MXFP4_K2(14) MXFP4_K2(15)
+#undef MXFP4_K2
         // every wave has fetched its last fragments of this buffer, and this wave's loads of the
         // next stage have landed: after the barrier the buffer may be refilled and the other read
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // (the three prefetch loads of this stage are younger than those and may still be out)
+        if (kRefill)
+            asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (decltype(refill)::value) issue_stage(s + 2, buf);
-        if (decltype(has_next)::value) {
-            read_frags(buf ^ 1, 0, 0);
-            read_scales(buf ^ 1, sa_nxt, sb_nxt);
-        }
-        MXFP4_MMA_STEP(1, 3, sa_cur, sb_cur)
-        __builtin_amdgcn_sched_barrier(0);
-        if (decltype(has_next)::value) {
+#define MXFP4_K3(N)                                                        \
+        if (kNext && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                \
+        if (kNext && (N) >= 8) read_scale_one(s + 1, (N) - 8);             \
+        if (kRefill && ((N) & 1)) issue_load(s + 2, buf, (N) >> 1);        \
+        if (kRefill && (N) == 14) issue_scales(((s + 1) >> 2) + 1, (s + 1) & 3); \
+        MXFP4_MMA(1, 3, N) MXFP4_PIN()
+        MXFP4_K3(0) MXFP4_K3(1) MXFP4_K3(2) MXFP4_K3(3) MXFP4_K3(4) MXFP4_K3(5) MXFP4_K3(6) MXFP4_K3(7)
+        MXFP4_K3(8) MXFP4_K3(9) MXFP4_K3(10) MXFP4_K3(11) MXFP4_K3(12) MXFP4_K3(13) MXFP4_K3(14) MXFP4_K3(15)
+#undef MXFP4_K3
+        if (kNext) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                sa_cur[i] = sa_nxt[i];
-                sb_cur[i] = sb_nxt[i];
+            for (int i = 0; i < 4; ++i) {  // bytes of each result: K blocks fh, 2+fh, 4+fh, 6+fh of the row
+                sa_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i].y, sraw[2 * i].x, perm_sel);
+                sb_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i + 1].y, sraw[2 * i + 1].x, perm_sel);
             }
         }
     };
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     for (int s = 0; s + 2 < nstages; ++s) stage(s, yes{}, yes{});
-    if (nstages >= 2) stage(nstages - 2, no{}, yes{});
+    stage(nstages - 2, no{}, yes{});
     stage(nstages - 1, no{}, no{});
-#undef MXFP4_MMA_STEP
+    asm volatile("" ::"v"(pf0), "v"(pf1), "v"(pf2));  // the prefetch registers were live until here
+#undef MXFP4_MMA
+#undef MXFP4_PIN
 
-    // ---- epilogue: lane owns row fr of each 32-row group and 4 x 4 consecutive columns ----------
+    // ---- epilogue -------------------------------------------------------------------------------
+    // A lane owns row fr of each 32-row group and, per 32-column group, columns 8*q + 4*fh + {0..3}.
+    // Stage the wave's sub-tile in its own LDS slice (skewed rows: conflict-free both ways), then
+    // write it out as whole row segments.
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();  // all waves are done reading fragments: the stage buffers are free
+    uint8_t *epi = smem + wave * EPI_WAVE_BYTES;
+    const int64_t row0 = m0 + wm * 128, col0 = n0 + wn * 128;
+    if (!OUT_FP32) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t row = m0 + wm * 128 + i * 32 + fr;
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const int64_t col = n0 + wn * 128 + j * 32 + 8 * qd + 4 * fh;
-                float v0 = acc[i][j][4 * qd + 0], v1 = acc[i][j][4 * qd + 1], v2 = acc[i][j][4 * qd + 2],
-                      v3 = acc[i][j][4 * qd + 3];
-                if (OUT_FP32) {
-                    v4f *o = reinterpret_cast<v4f *>(reinterpret_cast<float *>(out) + row * ld + col);
-                    if (ACC) {
-                        v4f old = *o;
-                        v0 += old.x; v1 += old.y; v2 += old.z; v3 += old.w;
-                    }
-                    *o = (v4f){v0, v1, v2, v3};
-                } else {
+                for (int qd = 0; qd < 4; ++qd) {
                     uint2 pk;
-                    pk.x = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
-                    pk.y = (uint32_t)f32_to_bf16(v2) | ((uint32_t)f32_to_bf16(v3) << 16);
-                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + row * ld + col) = pk;
+                    pk.x = pack_bf16(acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1]);
+                    pk.y = pack_bf16(acc[i][j][4 * qd + 2], acc[i][j][4 * qd + 3]);
+                    *reinterpret_cast<uint2 *>(epi + (i * 32 + fr) * EPI_PITCH_BF16 +
+                                               (j * 32 + 8 * qd + 4 * fh) * 2) = pk;
+                    if (qd == 3) __builtin_amdgcn_sched_barrier(0);  // one 32x32 tile at a time: few live registers
                 }
+        // 16 lanes x 16 bytes = one 256-byte row segment; 4 rows per instruction
+        const int rl = lane >> 4, ch = lane & 15;
+#pragma unroll 8
+        for (int r = 0; r < 128; r += 4) {
+            const v4i v = *reinterpret_cast<const v4i *>(epi + (r + rl) * EPI_PITCH_BF16 + ch * 16);
+            *reinterpret_cast<v4i *>(reinterpret_cast<uint16_t *>(out) + (row0 + r + rl) * ld + col0 + ch * 8) = v;
+        }
+    } else {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        const int i = half * 2 + ii;
+                        *reinterpret_cast<v4f *>(epi + (ii * 32 + fr) * EPI_PITCH_F32 +
+                                                 (j * 32 + 8 * qd + 4 * fh) * 4) =
+                            (v4f){acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1], acc[i][j][4 * qd + 2],
+                                  acc[i][j][4 * qd + 3]};
+                        if (qd == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+            // 32 lanes x 16 bytes = one 512-byte row segment; 2 rows per instruction
+            const int rl = lane >> 5, ch = lane & 31;
+#pragma unroll 8
+            for (int r = 0; r < 64; r += 2) {
+                v4f v = *reinterpret_cast<const v4f *>(epi + (r + rl) * EPI_PITCH_F32 + ch * 16);
+                v4f *o = reinterpret_cast<v4f *>(reinterpret_cast<float *>(out) + (row0 + half * 64 + r + rl) * ld +
+                                                 col0 + ch * 4);
+                if (ACC) v += *o;
+                *o = v;
             }
         }
     }
@@ -347,9 +477,11 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
 {
-    const bool tiled = g.C > 0 && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.C % STAGE_K) == 0 &&
-                       (g.ld % 4) == 0 && (reinterpret_cast<uintptr_t>(g.as) % 4) == 0 &&
-                       (reinterpret_cast<uintptr_t>(g.bs) % 4) == 0 && (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) &&
+    // the tiled kernel wants whole 256 x 256 tiles, K in whole 512s (at least 1024: scale bytes are
+    // fetched 32 per row, 16-byte aligned), and 16-byte aligned rows everywhere
+    const bool tiled = g.C >= 1024 && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.C % 512) == 0 &&
+                       (g.ld % 8) == 0 && (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 &&
+                       (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 && (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) &&
                        g.C < (int64_t(1) << 31);
     if (tiled) {
         const int tiles_m = (int)(g.Ra / TILE), tiles_n = (int)(g.Rb / TILE);

@@ -29,8 +29,10 @@ PEAK_FP4_TFLOPS = 10100.0  # MI355X dense MXFP4 MFMA peak
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 BYTES_PER_ELEM = 2.0 + 0.5 + 1.0 / 32.0  # bf16 read + packed codes + scale byte per element
 
-# HBM traffic per GEMM launch measured with `rocprofv3 --pmc` (see profiles/); None until measured
-GEMM_TRAFFIC_BYTES = None
+# Bytes crossing the L2's outward port per GEMM launch (mean of the three GEMMs), from the FETCH_SIZE and
+# WRITE_SIZE runs summarised in profiles/qkv_traffic_counters.md (FETCH_SIZE x 2.0 after calibration
+# against a 256 MiB copy)
+GEMM_TRAFFIC_BYTES = 260.0e6
 
 
 def event_time_ms(fn, iters, torch):
@@ -51,6 +53,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--counter-run", action="store_true",
+                    help="for rocprofv3 --pmc: one 256 MiB device copy (known traffic) followed by two "
+                         "steps of the workload, no timing, no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -83,6 +88,18 @@ def main() -> int:
     def step():
         mx.mxfp4_linear_fwd(x, w, cfg, y=y, workspace=ws_f)
         mx.mxfp4_linear_bwd(dy, x, w, cfg, dx=dx, dw=dw, workspace=ws_b)
+
+    if args.counter_run:
+        ref = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(ref)
+        ref.zero_()
+        torch.cuda.synchronize()
+        dst.copy_(ref)  # reference dispatch: reads 256 MiB, writes 256 MiB
+        step()
+        step()
+        torch.cuda.synchronize()
+        print("counter run done: reference copy 268435456 bytes each way, then 2 steps")
+        return 0
 
     for _ in range(args.warmup):
         step()
@@ -200,7 +217,7 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         import oracle
-        Ms = 512  # the first 512 of the 8192 tokens; all of N and K; all three stages
+        Ms = 4096  # the first 4096 of the 8192 tokens; all of N and K; all three stages
         xb, wb, dyb = synth.as_u16(x_cpu[:Ms]), synth.as_u16(w_cpu), synth.as_u16(dy_cpu[:Ms])
         c0 = time.perf_counter()
         oracle.linear_fwd(xb, wb, oracle.HAD_DET)

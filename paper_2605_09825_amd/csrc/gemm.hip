@@ -159,7 +159,6 @@ constexpr int SC_BUF_BYTES = 2 * SC_OP_BYTES;        // 16 KiB
 constexpr int OFF_SC = 2 * STAGE_BYTES;              // scale buffers behind the two stage buffers
 constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * SC_BUF_BYTES;  // 163840 = all of the CU's LDS
 constexpr int GROUP_M = 4;                      // tile rows per rasterisation group
-constexpr int PREFETCH_AHEAD = 4;               // stages between the L2 prefetch and the stage in use
 constexpr int EPI_PITCH_BF16 = 256 + 8;         // bytes per staged row of 128 bf16 (+ bank skew)
 constexpr int EPI_PITCH_F32 = 512 + 16;         // bytes per staged row of 128 fp32 (+ bank skew)
 constexpr int EPI_WAVE_BYTES = 33792;           // 128 x 264 = 64 x 528
@@ -238,31 +237,6 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
         const uint32_t dst = lds0 + OFF_SC + (b & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES +
                              (wave * 64 + (j & 1) * 32) * 32;
         dma16(dst, svoff, rows + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * 8);
-    };
-
-    // ---- L2 prefetch ---------------------------------------------------------------------------
-    // The operands do not fit the XCD's 4 MB L2, so each stage's lines come from the last-level
-    // cache or HBM with a latency of more than a stage.  The tiles running together on an XCD
-    // (4 tile rows x 8 tile columns, see the rasterisation above) share their A and B panels, so
-    // each pulls a 1/8 slice of its A panel and a 1/4 slice of its B panel of the stage
-    // PREFETCH_AHEAD ahead into L2 with ordinary loads whose results are never used (3 loads per
-    // wave and stage); the direct-to-LDS loads of all of them then hit in L2.  Purely a hint: a
-    // slice nobody fetched is just a slower load.  The destination registers are pinned for the
-    // whole loop ("+v") because the data arrives long after the instruction has issued.
-    const uint32_t pvoff = (uint32_t)((lane >> 3) * rowbytes) + (uint32_t)((lane & 7) << 4);
-    const uint8_t *a_pf = aq + (m0 + 32 * (tn & 7) + 8 * wave) * rowbytes;
-    const uint8_t *b_pf = bq + (n0 + 64 * (tm & 3) + 16 * wave) * rowbytes;
-    v4i pf0 = {0, 0, 0, 0}, pf1 = pf0, pf2 = pf0;
-    auto prefetch = [&](int s, int which) {
-        const int sp = (s + PREFETCH_AHEAD < nstages) ? s + PREFETCH_AHEAD : nstages - 1;
-        const int64_t koff = (int64_t)sp * (STAGE_K / 2);
-        if (which == 0)
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(pf0) : "v"(pvoff), "s"(a_pf + koff) : "memory");
-        else if (which == 1)
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(pf1) : "v"(pvoff), "s"(b_pf + koff) : "memory");
-        else
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(pf2) : "v"(pvoff), "s"(b_pf + 8 * rowbytes + koff)
-                         : "memory");
     };
 
     // ---- fragment reads: per-lane offsets ---------------------------------------------------
@@ -369,7 +343,6 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
 #undef MXFP4_K0
 #define MXFP4_K1(N)                                                        \
         if ((N) < 8) read_one(buf, 2, 0, (N));                             \
-        if (kRefill && ((N) == 9 || (N) == 11 || (N) == 13)) prefetch(s, ((N) - 9) >> 1); \
         MXFP4_MMA(1, 1, N) MXFP4_PIN()
         MXFP4_K1(0) MXFP4_K1(1) MXFP4_K1(2) MXFP4_K1(3) MXFP4_K1(4) MXFP4_K1(5) MXFP4_K1(6) MXFP4_K1(7)
         MXFP4_K1(8) MXFP4_K1(9) MXFP4_K1(10) MXFP4_K1(11) MXFP4_K1(12) MXFP4_K1(13) MXFP4_K1(14) MXFP4_K1(15)
@@ -382,11 +355,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
 #undef MXFP4_K2
         // every wave has fetched its last fragments of this buffer, and this wave's loads of the
         // next stage have landed: after the barrier the buffer may be refilled and the other read
-        // (the three prefetch loads of this stage are younger than those and may still be out)
-        if (kRefill)
-            asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
 #define MXFP4_K3(N)                                                        \
         if (kNext && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                \
@@ -410,7 +379,6 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
     for (int s = 0; s + 2 < nstages; ++s) stage(s, yes{}, yes{});
     stage(nstages - 2, no{}, yes{});
     stage(nstages - 1, no{}, no{});
-    asm volatile("" ::"v"(pf0), "v"(pf1), "v"(pf2));  // the prefetch registers were live until here
 #undef MXFP4_MMA
 #undef MXFP4_PIN
 

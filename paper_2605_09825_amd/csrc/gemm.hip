@@ -1,18 +1,19 @@
 // Block-scaled FP4 GEMM for gfx950: out[i][j] (+)= sum_c A[i][c] * B[j][c] on MXFP4
 // operands (the MXFP4 GEMM of the linear layers, Sec. 1 / App. A.2; operand axes per
-// App. C.1-C.3), on the scaled matrix instruction V_MFMA_SCALE_F32_16X16X128_F8F6F4.
+// App. C.1-C.3), on the scaled matrix instructions V_MFMA_SCALE_F32_{16X16X128,32X32X64}_F8F6F4.
 //
-// Register layout of that instruction with FP4 operands (64 lanes, lane = l):
-//   first operand  (16 x 128): lane l holds row  l%16, elements k = 32*(l/16) .. +31
-//                  as 16 bytes (4 VGPRs), element k in nibble k%32 (low nibble first);
-//                  its scale VGPR holds the E8M0 byte of exactly that 32-element block
-//   second operand (128 x 16): the same with "row" = output column
-//   result (16 x 16, 4 VGPRs): lane l holds column l%16, rows 4*(l/16) + {0,1,2,3}
+// Register layout of those instructions with FP4 operands (64 lanes, lane = l; n = 16 or 32 rows):
+//   first operand : lane l holds row l%n, the 32 K-elements 32*(l/n) .. +31 as 16 bytes
+//                   (4 VGPRs), element k in nibble k%32 (low nibble first); its scale VGPR holds
+//                   the E8M0 byte of exactly that 32-element block
+//   second operand: the same with "row" = output column
+//   result        : 16x16: lane l holds column l%16, rows 4*(l/16) + {0..3};
+//                   32x32: register e of lane l holds D[8*(e/4) + 4*(l/32) + e%4][l%32]
 // i.e. one lane's operand is precisely one MX block of the canonical layout, so the
 // canonical q/s arrays feed the instruction without any repacking.
 //
 // The kernels pass B's rows as the first operand and A's rows as the second: a lane
-// then owns 4 consecutive output columns of one output row (one 16- or 8-byte store).
+// then owns 4 consecutive output columns of one output row.
 #include <type_traits>
 
 #include "mxfp4_internal.h"

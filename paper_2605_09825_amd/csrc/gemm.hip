@@ -160,9 +160,7 @@ constexpr int SC_BUF_BYTES = 2 * SC_OP_BYTES;        // 16 KiB
 constexpr int OFF_SC = 2 * STAGE_BYTES;              // scale buffers behind the two stage buffers
 constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * SC_BUF_BYTES;  // 163840 = all of the CU's LDS
 constexpr int GROUP_M = 4;                      // tile rows per rasterisation group
-constexpr int EPI_PITCH_BF16 = 256 + 8;         // bytes per staged row of 128 bf16 (+ bank skew)
-constexpr int EPI_PITCH_F32 = 512 + 16;         // bytes per staged row of 128 fp32 (+ bank skew)
-constexpr int EPI_WAVE_BYTES = 33792;           // 128 x 264 = 64 x 528
+constexpr int NUM_CUS = 256;                    // MI355X: 8 XCDs x 32 CUs
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
@@ -172,6 +170,13 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const ui
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t" ::"s"(lds_addr), "v"(voff), "s"(sbase)
                  : "memory");
 }
+
+// Operand rows one wave loads for one tile: rows wave*64 .. +63 of the tile's A rows, B rows and
+// of their scale rows.
+struct TileSrc {
+    const uint8_t *a, *b, *as, *bs;
+    int64_t m0, n0;
+};
 
 template <bool OUT_FP32, bool ACC>
 __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__restrict__ aq,
@@ -187,55 +192,66 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
+    const int64_t rowbytes = C >> 1, nkb = C >> 5;
+    const int nstages = (int)(C / STAGE_K);  // even and >= 4 (the host checks C % 512 == 0, C >= 1024)
 
-    // workgroup id -> tile.  Ids are dealt round-robin to the 8 XCDs (each with its own L2): give
-    // every XCD a contiguous run of the tile sequence, and walk that sequence in groups of GROUP_M
-    // tile rows so that the tiles in flight on one XCD share A and B panels.
-    int tm, tn;
-    {
-        const int T = tiles_m * tiles_n, w = blockIdx.x;
-        const int per = T >> 3, rem = T & 7, xcd = w & 7, local = w >> 3;
-        const int L = xcd < rem ? xcd * (per + 1) + local : rem * (per + 1) + (xcd - rem) * per + local;
+    // ---- persistent tile schedule -----------------------------------------------------------
+    // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  XCD x owns a
+    // contiguous run of the tile sequence; its workgroups walk that run with a stride equal to
+    // their number, so the tiles in flight on one XCD are consecutive in the sequence, and the
+    // sequence goes through the tile grid in groups of GROUP_M tile rows: those tiles share
+    // A and B panels in the XCD's L2.
+    const int T = tiles_m * tiles_n, G = (int)gridDim.x;
+    const int xcd = blockIdx.x & 7, lw = blockIdx.x >> 3;
+    const int nwg_x = (G - xcd + 7) >> 3;                      // workgroups living on this XCD
+    const int per = T >> 3, rem = T & 7;
+    const int count_x = per + (xcd < rem ? 1 : 0);             // tiles owned by this XCD
+    const int start_x = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+    auto tile_src = [&](int lloc) {
+        const int L = start_x + lloc;
         const int span = GROUP_M * tiles_n, grp = L / span, first = grp * GROUP_M;
         const int gm = (tiles_m - first) < GROUP_M ? (tiles_m - first) : GROUP_M;
         const int in = L - grp * span;
-        tm = first + in % gm;
-        tn = in / gm;
-    }
-    const int64_t rowbytes = C >> 1, nkb = C >> 5;
-    const int nstages = (int)(C / STAGE_K);
-    const int64_t m0 = (int64_t)tm * TILE, n0 = (int64_t)tn * TILE;
+        TileSrc t;
+        t.m0 = (int64_t)(first + in % gm) * TILE;
+        t.n0 = (int64_t)(in / gm) * TILE;
+        t.a = aq + (t.m0 + wave * 64) * rowbytes;
+        t.b = bq + (t.n0 + wave * 64) * rowbytes;
+        t.as = as + (t.m0 + wave * 64) * nkb;
+        t.bs = bs + (t.n0 + wave * 64) * nkb;
+        return t;
+    };
+    if (lw >= count_x) return;  // (whole workgroup: nothing to do)
 
     // ---- direct-to-LDS loads: per-lane offsets (fixed for the whole kernel) -----------------
     const int drr = lane >> 3, dcc = lane & 7;
     const uint32_t dvoff0 = (uint32_t)(drr * rowbytes) + (uint32_t)((dcc ^ drr) << 4);        // even 8-row groups
     const uint32_t dvoff1 = (uint32_t)(drr * rowbytes) + (uint32_t)((dcc ^ drr ^ 1) << 4);    // odd ones
     const uint32_t svoff = (uint32_t)((lane >> 1) * nkb) + (uint32_t)((lane & 1) << 4);
-    const uint8_t *a_rows = aq + (m0 + wave * 64) * rowbytes;  // this wave loads rows wave*64 .. +63 of each tile
-    const uint8_t *b_rows = bq + (n0 + wave * 64) * rowbytes;
-    const uint8_t *as_rows = as + (m0 + wave * 64) * nkb;
-    const uint8_t *bs_rows = bs + (n0 + wave * 64) * nkb;
 
-    // load n (0..15) of stage s for this wave: even n -> A, odd n -> B; 8-row group n/2 of the wave's 64 rows
-    auto issue_load = [&](int s, int buf, int n) {
+    // load n (0..15) of stage s of tile t for this wave: even n -> A, odd n -> B; 8-row group n/2 of
+    // the wave's 64 rows
+    auto issue_load = [&](const TileSrc &t, int s, int buf, int n) {
         const uint32_t base = lds0 + buf * STAGE_BYTES;
         const int64_t koff = (int64_t)s * (STAGE_K / 2);
         const int g = n >> 1;
         const uint32_t dst = (uint32_t)((wave * 8 + g) * 1024);
         const uint32_t vo = (g & 1) ? dvoff1 : dvoff0;
         if (n & 1)
-            dma16(base + OFF_B + dst, vo, b_rows + g * 8 * rowbytes + koff);
+            dma16(base + OFF_B + dst, vo, t.b + g * 8 * rowbytes + koff);
         else
-            dma16(base + OFF_A + dst, vo, a_rows + g * 8 * rowbytes + koff);
+            dma16(base + OFF_A + dst, vo, t.a + g * 8 * rowbytes + koff);
     };
     // Scale batch b holds the 32 scale bytes per row of stages first(b) .. first(b)+3, where
     // first(b) = min(4b, nstages-4): the last batch is pulled back so that it never reads past a
     // row's end (batches past the end of K just repeat the last one into the idle buffer).
     auto batch_first = [&](int b) { return (4 * b < nstages - 4) ? 4 * b : nstages - 4; };
     // instruction j (0..3) of batch b for this wave: j>>1 = operand, j&1 = which 32 of its 64 rows
-    auto issue_scales = [&](int b, int j) {
-        const uint8_t *rows = (j >> 1) ? bs_rows : as_rows;
-        const uint32_t dst = lds0 + OFF_SC + (b & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES +
+    // Batch b of a tile lives in scale buffer (b ^ par) & 1; par alternates between tiles so that
+    // a tile's first batch never lands in the buffer its predecessor's last batch is still read from.
+    auto issue_scales = [&](const TileSrc &t, int b, int j, int par) {
+        const uint8_t *rows = (j >> 1) ? t.bs : t.as;
+        const uint32_t dst = lds0 + OFF_SC + ((b ^ par) & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES +
                              (wave * 64 + (j & 1) * 32) * 32;
         dma16(dst, svoff, rows + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * 8);
     };
@@ -252,59 +268,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
     const uint32_t perm_sel = fh ? 0x07050301u : 0x06040200u;
 
     v4i fa[2][4], fb[2][4];
-    auto read_frags = [&](int buf, int kk, int set) {
-        const uint8_t *p = smem + buf * STAGE_BYTES + foff[kk];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[set][i] = *reinterpret_cast<const v4i *>(p + a_frag0 + i * 4096);
-            fb[set][i] = *reinterpret_cast<const v4i *>(p + b_frag0 + i * 4096);
-        }
-    };
-    auto read_scales = [&](int s, int (&sa)[4], int (&sb)[4]) {
-        const int b = s >> 2;
-        const uint8_t *p = smem + (b & 1) * SC_BUF_BYTES + (s - batch_first(b)) * 8;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint2 a = *reinterpret_cast<const uint2 *>(p + sa_frag0 + i * 1024);
-            const uint2 bb = *reinterpret_cast<const uint2 *>(p + sb_frag0 + i * 1024);
-            sa[i] = (int)__builtin_amdgcn_perm(a.y, a.x, perm_sel);  // bytes: K blocks fh, 2+fh, 4+fh, 6+fh
-            sb[i] = (int)__builtin_amdgcn_perm(bb.y, bb.x, perm_sel);
-        }
-    };
-
-    v16f acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    // One matrix instruction: tile (n/4, n%4) of the wave's 4 x 4, fragments from register set SET,
-    // K-step KK selects the scale byte.
-#define MXFP4_MMA(SET, KK, N)                                                                                   \
-    {                                                                                                           \
-        constexpr int i_ = (N) >> 2, j_ = (N) & 3;                                                              \
-        v8i fb8 = {fb[SET][j_].x, fb[SET][j_].y, fb[SET][j_].z, fb[SET][j_].w, 0, 0, 0, 0};                     \
-        v8i fa8 = {fa[SET][i_].x, fa[SET][i_].y, fa[SET][i_].z, fa[SET][i_].w, 0, 0, 0, 0};                     \
-        acc[i_][j_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8, fa8, acc[i_][j_], 4, 4, KK,          \
-                                                                      sb_cur[j_], KK, sa_cur[i_]);              \
-    }
-
+    uint2 sraw[8];
     int sa_cur[4], sb_cur[4];
-    // prologue: all of stage 0, the first 8 loads of stage 1, scale batch 0 and the first load of batch 1
-#pragma unroll
-    for (int n = 0; n < 16; ++n) issue_load(0, 0, n);
-#pragma unroll
-    for (int n = 0; n < 8; ++n) issue_load(1, 1, n);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) issue_scales(0, j);
-    issue_scales(1, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    read_frags(0, 0, 0);
-    read_scales(0, sa_cur, sb_cur);
-
     // One fragment fetch (f = 0..7: A0,B0,A1,B1,...) of K-step kk of buffer buf into register set `set`.
     auto read_one = [&](int buf, int kk, int set, int f) {
         const uint8_t *p = smem + buf * STAGE_BYTES + foff[kk] + (f >> 1) * 4096;
@@ -313,12 +278,36 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
         else
             fa[set][f >> 1] = *reinterpret_cast<const v4i *>(p + a_frag0);
     };
-    uint2 sraw[8];
-    auto read_scale_one = [&](int s, int f) {  // f = 0..7: A0,B0,A1,B1,...
+    // The 8 scale bytes of stage s for fragment row f (0..7: A0,B0,A1,B1,...), raw.
+    auto read_scale_one = [&](int s, int f, int par) {
         const int b = s >> 2;
-        const uint8_t *p = smem + (b & 1) * SC_BUF_BYTES + (s - batch_first(b)) * 8 + (f >> 1) * 1024;
+        const uint8_t *p = smem + ((b ^ par) & 1) * SC_BUF_BYTES + (s - batch_first(b)) * 8 + (f >> 1) * 1024;
         sraw[f] = *reinterpret_cast<const uint2 *>(p + ((f & 1) ? sb_frag0 : sa_frag0));
     };
+    // raw scale bytes -> one register per fragment row whose bytes are K blocks fh, 2+fh, 4+fh, 6+fh
+    auto permute_scales = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sa_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i].y, sraw[2 * i].x, perm_sel);
+            sb_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i + 1].y, sraw[2 * i + 1].x, perm_sel);
+        }
+    };
+
+    v16f acc[4][4];
+    const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // One matrix instruction: tile (n/4, n%4) of the wave's 4 x 4, fragments from register set SET,
+    // K-step KK selects the scale byte.
+#define MXFP4_MMA(SET, KK, N, FRESH)                                                                            \
+    {                                                                                                           \
+        constexpr int i_ = (N) >> 2, j_ = (N) & 3;                                                              \
+        v8i fb8 = {fb[SET][j_].x, fb[SET][j_].y, fb[SET][j_].z, fb[SET][j_].w, 0, 0, 0, 0};                     \
+        v8i fa8 = {fa[SET][i_].x, fa[SET][i_].y, fa[SET][i_].z, fa[SET][i_].w, 0, 0, 0, 0};                     \
+        acc[i_][j_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8, fa8, (FRESH) ? zero16 : acc[i_][j_], \
+                                                                      4, 4, KK, sb_cur[j_], KK, sa_cur[i_]);    \
+    }
+#define MXFP4_PIN() __builtin_amdgcn_sched_barrier(0);
+#define MXFP4_16(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)
 
     // One stage = 4 K-steps of 16 matrix instructions.  Everything else is threaded between them,
     // one item per matrix instruction, and pinned there with scheduling barriers: with a single
@@ -329,117 +318,170 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
     //   barrier (this stage's buffer is free, the next stage has landed)
     //   K-step 3: fragments + scales of the next stage's K-step 0; first half of the loads of
     //             the stage after next, into the buffer just freed; one scale load
-    // The loop body must stay one basic block (no data-dependent branches), or the matrix
-    // instructions get sunk behind the branches; the last two stages are peeled instead.
-#define MXFP4_PIN() __builtin_amdgcn_sched_barrier(0);
-    auto stage = [&](int s, auto refill, auto has_next) {
+    // The main loop's body must stay one basic block (no data-dependent branches), or the matrix
+    // instructions get sunk behind the branches; so the last two stages of a tile, which hand
+    // over to the next tile, are separate instantiations (MODE 1 and 2).
+    //   MODE 3: stage 0: as MODE 0, and its first K-step starts the accumulators from zero
+    //   MODE 0: stage 1 <= s <= nstages-3 of tile `cur`
+    //   MODE 1: stage nstages-2: its K-step 3 starts loading stage 0 and scale batch 0 of tile `nxt`
+    //   MODE 2: stage nstages-1: its K-step 0 finishes stage 0; K-step 3 issues the first load of
+    //           nxt's scale batch 1 and fetches nothing (the epilogue follows)
+    auto stage = [&](const TileSrc &cur, const TileSrc &nxt, int par, int par_nxt, int s, auto mode) {
+        constexpr int MODE = decltype(mode)::value;
         const int buf = s & 1;
-        constexpr bool kRefill = decltype(refill)::value, kNext = decltype(has_next)::value;
-#define MXFP4_K0(N)                                                        \
-        if ((N) < 8) read_one(buf, 1, 1, (N));                             \
-        if (kNext && ((N) & 1)) issue_load(s + 1, buf ^ 1, 8 + ((N) >> 1)); \
-        MXFP4_MMA(0, 0, N) MXFP4_PIN()
-        MXFP4_K0(0) MXFP4_K0(1) MXFP4_K0(2) MXFP4_K0(3) MXFP4_K0(4) MXFP4_K0(5) MXFP4_K0(6) MXFP4_K0(7)
-        MXFP4_K0(8) MXFP4_K0(9) MXFP4_K0(10) MXFP4_K0(11) MXFP4_K0(12) MXFP4_K0(13) MXFP4_K0(14) MXFP4_K0(15)
+#define MXFP4_K0(N)                                                                              \
+        if ((N) < 8) read_one(buf, 1, 1, (N));                                                   \
+        if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, 8 + ((N) >> 1));              \
+        if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, 8 + ((N) >> 1));      \
+        MXFP4_MMA(0, 0, N, MODE == 3) MXFP4_PIN()
+        MXFP4_16(MXFP4_K0)
 #undef MXFP4_K0
-#define MXFP4_K1(N)                                                        \
-        if ((N) < 8) read_one(buf, 2, 0, (N));                             \
-        MXFP4_MMA(1, 1, N) MXFP4_PIN()
-        MXFP4_K1(0) MXFP4_K1(1) MXFP4_K1(2) MXFP4_K1(3) MXFP4_K1(4) MXFP4_K1(5) MXFP4_K1(6) MXFP4_K1(7)
-        MXFP4_K1(8) MXFP4_K1(9) MXFP4_K1(10) MXFP4_K1(11) MXFP4_K1(12) MXFP4_K1(13) MXFP4_K1(14) MXFP4_K1(15)
+#define MXFP4_K1(N)                                                                              \
+        if ((N) < 8) read_one(buf, 2, 0, (N));                                                   \
+        MXFP4_MMA(1, 1, N, false) MXFP4_PIN()
+        MXFP4_16(MXFP4_K1)
 #undef MXFP4_K1
-#define MXFP4_K2(N)                                                        \
-        if ((N) < 8) read_one(buf, 3, 1, (N));                             \
-        MXFP4_MMA(0, 2, N) MXFP4_PIN()
-        MXFP4_K2(0) MXFP4_K2(1) MXFP4_K2(2) MXFP4_K2(3) MXFP4_K2(4) MXFP4_K2(5) MXFP4_K2(6) MXFP4_K2(7)
-        MXFP4_K2(8) MXFP4_K2(9) MXFP4_K2(10) MXFP4_K2(11) MXFP4_K2(12) MXFP4_K2(13) MXFP4_K2(14) MXFP4_K2(15)
+#define MXFP4_K2(N)                                                                              \
+        if ((N) < 8) read_one(buf, 3, 1, (N));                                                   \
+        MXFP4_MMA(0, 2, N, false) MXFP4_PIN()
+        MXFP4_16(MXFP4_K2)
 #undef MXFP4_K2
         // every wave has fetched its last fragments of this buffer, and this wave's loads of the
         // next stage have landed: after the barrier the buffer may be refilled and the other read
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-#define MXFP4_K3(N)                                                        \
-        if (kNext && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                \
-        if (kNext && (N) >= 8) read_scale_one(s + 1, (N) - 8);             \
-        if (kRefill && ((N) & 1)) issue_load(s + 2, buf, (N) >> 1);        \
-        if (kRefill && (N) == 14) issue_scales(((s + 1) >> 2) + 1, (s + 1) & 3); \
-        MXFP4_MMA(1, 3, N) MXFP4_PIN()
-        MXFP4_K3(0) MXFP4_K3(1) MXFP4_K3(2) MXFP4_K3(3) MXFP4_K3(4) MXFP4_K3(5) MXFP4_K3(6) MXFP4_K3(7)
-        MXFP4_K3(8) MXFP4_K3(9) MXFP4_K3(10) MXFP4_K3(11) MXFP4_K3(12) MXFP4_K3(13) MXFP4_K3(14) MXFP4_K3(15)
+#define MXFP4_K3(N)                                                                              \
+        if (MODE != 2 && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                                   \
+        if (MODE != 2 && (N) >= 8) read_scale_one(s + 1, (N) - 8, par);                           \
+        if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, (N) >> 1);                       \
+        if ((MODE == 0 || MODE == 3) && (N) == 14) issue_scales(cur, ((s + 1) >> 2) + 1, (s + 1) & 3, par); \
+        if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, (N) >> 1);                \
+        if (MODE == 1 && !((N) & 1) && (N) < 8) issue_scales(nxt, 0, (N) >> 1, par_nxt);         \
+        if (MODE == 2 && (N) == 1) issue_scales(nxt, 1, 0, par_nxt);                             \
+        MXFP4_MMA(1, 3, N, false) MXFP4_PIN()
+        MXFP4_16(MXFP4_K3)
 #undef MXFP4_K3
-        if (kNext) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {  // bytes of each result: K blocks fh, 2+fh, 4+fh, 6+fh of the row
-                sa_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i].y, sraw[2 * i].x, perm_sel);
-                sb_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i + 1].y, sraw[2 * i + 1].x, perm_sel);
-            }
-        }
+        if (MODE != 2) permute_scales();
     };
-    using yes = std::integral_constant<bool, true>;
-    using no = std::integral_constant<bool, false>;
-    for (int s = 0; s + 2 < nstages; ++s) stage(s, yes{}, yes{});
-    stage(nstages - 2, no{}, yes{});
-    stage(nstages - 1, no{}, no{});
-#undef MXFP4_MMA
-#undef MXFP4_PIN
+    using mode_main = std::integral_constant<int, 0>;
+    using mode_penult = std::integral_constant<int, 1>;
+    using mode_last = std::integral_constant<int, 2>;
+    using mode_first = std::integral_constant<int, 3>;
 
-    // ---- epilogue -------------------------------------------------------------------------------
-    // A lane owns row fr of each 32-row group and, per 32-column group, columns 8*q + 4*fh + {0..3}.
-    // Stage the wave's sub-tile in its own LDS slice (skewed rows: conflict-free both ways), then
-    // write it out as whole row segments.
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();  // all waves are done reading fragments: the stage buffers are free
-    uint8_t *epi = smem + wave * EPI_WAVE_BYTES;
-    const int64_t row0 = m0 + wm * 128, col0 = n0 + wn * 128;
-    if (!OUT_FP32) {
+    // ---- first tile: fill the pipeline --------------------------------------------------------
+    // all of stage 0, the first 8 loads of stage 1, scale batch 0 and the first load of batch 1
+    TileSrc cur = tile_src(lw);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+    for (int n = 0; n < 16; ++n) issue_load(cur, 0, 0, n);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 4; ++j) issue_scales(cur, 0, j, 0);
+    issue_scales(cur, 1, 0, 0);
+    int par = 0;
+    const int b_last = (nstages - 1) >> 2;
+
+    for (int lloc = lw; lloc < count_x; lloc += nwg_x) {
+        const int par_nxt = (b_last ^ par ^ 1) & 1;
+        // the tile after this one; after the last tile the hand-over loads simply fetch that tile's
+        // first stage again into buffers that are idle by then (no branches in the stage bodies)
+        const TileSrc nxt = (lloc + nwg_x < count_x) ? tile_src(lloc + nwg_x) : cur;
+        // entering a tile: its stage 0 and first scale batch have landed (first tile: wait for them
+        // here); after the barrier start stage 1's first half and fetch the first fragments
+        if (lloc == lw) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");  // (later tiles waited before the epilogue)
+        __syncthreads();
 #pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    uint2 pk;
-                    pk.x = pack_bf16(acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1]);
-                    pk.y = pack_bf16(acc[i][j][4 * qd + 2], acc[i][j][4 * qd + 3]);
-                    *reinterpret_cast<uint2 *>(epi + (i * 32 + fr) * EPI_PITCH_BF16 +
-                                               (j * 32 + 8 * qd + 4 * fh) * 2) = pk;
-                    if (qd == 3) __builtin_amdgcn_sched_barrier(0);  // one 32x32 tile at a time: few live registers
-                }
-        // 16 lanes x 16 bytes = one 256-byte row segment; 4 rows per instruction
-        const int rl = lane >> 4, ch = lane & 15;
-#pragma unroll 8
-        for (int r = 0; r < 128; r += 4) {
-            const v4i v = *reinterpret_cast<const v4i *>(epi + (r + rl) * EPI_PITCH_BF16 + ch * 16);
-            *reinterpret_cast<v4i *>(reinterpret_cast<uint16_t *>(out) + (row0 + r + rl) * ld + col0 + ch * 8) = v;
+        for (int n = 0; n < 8; ++n) issue_load(cur, 1, 1, n);
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+            read_one(0, 0, 0, f);
+            read_scale_one(0, f, par);
         }
-    } else {
+        permute_scales();
+
+        stage(cur, nxt, par, par_nxt, 0, mode_first{});
+        for (int s = 1; s + 2 < nstages; ++s) stage(cur, nxt, par, par_nxt, s, mode_main{});
+        stage(cur, nxt, par, par_nxt, nstages - 2, mode_penult{});
+        stage(cur, nxt, par, par_nxt, nstages - 1, mode_last{});
+        __builtin_amdgcn_sched_barrier(0);
+        // the next tile's stage 0 and scale batch 0 have been on their way for at least two K-steps: make
+        // sure they have landed now, before any store is issued (only the one scale load of batch 1 issued
+        // a moment ago may stay out), so that nothing later has to wait for the stores to drain
+        asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+
+        // ---- epilogue ---------------------------------------------------------------------------
+        // A lane owns row fr of each 32-row group and, per 32-column group, columns 8*q + 4*fh + {0..3}.
+        // Stage buffer 1 is free (all waves passed the last barrier; buffer 0 may already hold the next
+        // tile's stage 0): each wave transposes its sub-tile through its own 16 KiB slice of it, 64
+        // (bf16) or 32 (fp32) rows at a time, and writes whole 256- / 512-byte row segments.  Rows are
+        // stored unpadded; 16-byte chunk c of row r sits at chunk c ^ (r & 15) (bf16: and its two 8-byte
+        // halves swap when r & 16), which keeps both the 8/16-byte writes and the 16-byte reads
+        // conflict-free.
+        uint8_t *epi = smem + STAGE_BYTES + wave * 16384;
+        const int64_t row0 = cur.m0 + wm * 128, col0 = cur.n0 + wn * 128;
+        if (!OUT_FP32) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
+            for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
-            for (int ii = 0; ii < 2; ++ii)
+                for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int qd = 0; qd < 4; ++qd) {
+                            const int i = 2 * pass + ii;
+                            const int r = ii * 32 + fr, c = j * 4 + qd;
+                            uint2 pk;
+                            pk.x = pack_bf16(acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1]);
+                            pk.y = pack_bf16(acc[i][j][4 * qd + 2], acc[i][j][4 * qd + 3]);
+                            *reinterpret_cast<uint2 *>(epi + r * 256 + ((c ^ (r & 15)) << 4) +
+                                                       ((fh ^ ((r >> 4) & 1)) << 3)) = pk;
+                            if (qd == 3) __builtin_amdgcn_sched_barrier(0);  // one 32x32 tile at a time
+                        }
+                // 16 lanes x 16 bytes = one 256-byte row segment; 4 rows per instruction
+                const int rl = lane >> 4, ch = lane & 15;
+#pragma unroll
+                for (int r4 = 0; r4 < 64; r4 += 4) {
+                    const int r = r4 + rl;
+                    v4i v = *reinterpret_cast<const v4i *>(epi + r * 256 + ((ch ^ (r & 15)) << 4));
+                    if ((r4 >> 4) & 1) v = (v4i){v.z, v.w, v.x, v.y};
+                    *reinterpret_cast<v4i *>(reinterpret_cast<uint16_t *>(out) + (row0 + pass * 64 + r) * ld + col0 +
+                                             ch * 8) = v;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int qd = 0; qd < 4; ++qd) {
-                        const int i = half * 2 + ii;
-                        *reinterpret_cast<v4f *>(epi + (ii * 32 + fr) * EPI_PITCH_F32 +
-                                                 (j * 32 + 8 * qd + 4 * fh) * 4) =
-                            (v4f){acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1], acc[i][j][4 * qd + 2],
-                                  acc[i][j][4 * qd + 3]};
+                        const int c = j * 8 + qd * 2 + fh;
+                        *reinterpret_cast<v4f *>(epi + fr * 512 + ((c ^ fr) << 4)) =
+                            (v4f){acc[pass][j][4 * qd + 0], acc[pass][j][4 * qd + 1], acc[pass][j][4 * qd + 2],
+                                  acc[pass][j][4 * qd + 3]};
                         if (qd == 3) __builtin_amdgcn_sched_barrier(0);
                     }
-            // 32 lanes x 16 bytes = one 512-byte row segment; 2 rows per instruction
-            const int rl = lane >> 5, ch = lane & 31;
-#pragma unroll 8
-            for (int r = 0; r < 64; r += 2) {
-                v4f v = *reinterpret_cast<const v4f *>(epi + (r + rl) * EPI_PITCH_F32 + ch * 16);
-                v4f *o = reinterpret_cast<v4f *>(reinterpret_cast<float *>(out) + (row0 + half * 64 + r + rl) * ld +
-                                                 col0 + ch * 4);
-                if (ACC) v += *o;
-                *o = v;
+                // 32 lanes x 16 bytes = one 512-byte row segment; 2 rows per instruction
+                const int rl = lane >> 5, ch = lane & 31;
+#pragma unroll
+                for (int r2 = 0; r2 < 32; r2 += 2) {
+                    const int r = r2 + rl;
+                    v4f v = *reinterpret_cast<const v4f *>(epi + r * 512 + ((ch ^ r) << 4));
+                    v4f *o = reinterpret_cast<v4f *>(reinterpret_cast<float *>(out) + (row0 + pass * 32 + r) * ld +
+                                                     col0 + ch * 4);
+                    if (ACC) v += *o;
+                    *o = v;
+                }
             }
         }
+        // (the barrier at the top of the loop keeps the next tile's loads out of stage buffer 1 until
+        // every wave is done reading its slice)
+        cur = nxt;
+        par = par_nxt;
     }
+    // nothing may still be writing this workgroup's LDS when it retires
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef MXFP4_MMA
+#undef MXFP4_PIN
+#undef MXFP4_16
 }
 
 }  // namespace
@@ -454,7 +496,9 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
                        g.C < (int64_t(1) << 31);
     if (tiled) {
         const int tiles_m = (int)(g.Ra / TILE), tiles_n = (int)(g.Rb / TILE);
-        dim3 grid((unsigned)(tiles_m * tiles_n));
+        // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
+        const int T = tiles_m * tiles_n;
+        dim3 grid((unsigned)(T < NUM_CUS ? T : NUM_CUS));
         if (g.out_fp32) {
             if (g.accumulate)
                 hipLaunchKernelGGL((gemm_tile_kernel<true, true>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs,

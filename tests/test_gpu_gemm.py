@@ -37,7 +37,8 @@ def assert_close(got, want, absum):
 
 
 @pytest.mark.parametrize("shape", [(64, 64, 128), (16, 16, 32), (37, 53, 96), (1, 1, 32), (256, 512, 512),
-                                   (130, 70, 1024), (512, 384, 4096), (100, 260, 160)])
+                                   (130, 70, 1024), (512, 384, 4096), (100, 260, 160), (512, 768, 1536),
+                                   (256, 256, 1024), (768, 512, 2560)])
 def test_random_codes_fp32(shape):
     Ra, Rb, C = shape
     rng = np.random.default_rng(Ra * 7 + Rb * 3 + C)
@@ -133,6 +134,24 @@ def sample_positions(rng, Ra, Rb, n_rows=4, n_cols=4, n_tiles=24):
         ii += list((r0 + g[0]).ravel())
         jj += list((c0 + g[1]).ravel())
     return np.array(ii, dtype=np.int64), np.array(jj, dtype=np.int64)
+
+
+@pytest.mark.parametrize("out_dtype", [mx.OUT_FP32, mx.OUT_BF16])
+def test_many_tiles_per_workgroup_sampled(out_dtype):
+    # 17 x 17 = 289 tiles of 256 x 256 (more than one per CU, not a multiple of 8), 4 K-stages
+    Ra = Rb = 256 * 17
+    C = 1024
+    rng = np.random.default_rng(5)
+    aq, as_ = rand_operand(rng, Ra, C)
+    bq, bs = rand_operand(rng, Rb, C)
+    out = run_gemm(aq, as_, bq, bs, out_dtype=out_dtype)
+    ii, jj = sample_positions(rng, Ra, Rb, n_rows=3, n_cols=3, n_tiles=64)
+    want, absum = oracle.gemm_at(aq, as_, bq, bs, ii, jj)
+    got = out.float().cpu().numpy()[ii, jj]
+    if out_dtype == mx.OUT_FP32:
+        assert_close(got, want, absum)
+    else:
+        assert (np.abs(got - want) <= 1e-5 * absum + 2.0**-8 * np.abs(want)).all()
 
 
 def test_config2_shape_sampled():

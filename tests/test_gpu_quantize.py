@@ -133,3 +133,19 @@ def test_config4_wgrad_operands_full_size():
     check(dy, mx.AXIS_FIRST, mx.HAD_NONE, mx.SR, seed=4)
     x = synth.normal(16384, 14336, 1.0, 0, synth.STREAM_X)
     check(x, mx.AXIS_FIRST, mx.HAD_DET, mx.RNE)
+
+
+def test_more_than_2_32_elements_stochastic_rounding_counters():
+    # 131104 x 32768 = 4.296e9 elements (8.6 GB of bf16): block and byte offsets beyond 2^31 and
+    # stochastic-rounding counters beyond 2^32 (the high word of the counter enters the hash)
+    rows, cols = 131072 + 32, 32768
+    block = synth.as_u16(synth.normal(4097, cols, 1.0, 12, synth.STREAM_X))
+    x = np.tile(block, (32, 1))
+    assert x.shape == (rows, cols) and x.size > 2**32
+    t = synth.from_bits(x)
+    q, s = gpu_quantize(t, mx.AXIS_LAST, mx.HAD_NONE, mx.SR, seed=77)
+    qo, so = oracle.quantize(x, oracle.AXIS_LAST, oracle.HAD_NONE, oracle.SR, 77)
+    assert np.array_equal(s, so)
+    assert np.array_equal(q, qo), "codes: " + first_mismatch(q, qo)
+    # the same values at different positions round differently (the counter, not the value, decides)
+    assert not np.array_equal(q[:4097], q[-4097:])

@@ -32,7 +32,7 @@ BYTES_PER_ELEM = 2.0 + 0.5 + 1.0 / 32.0  # bf16 read + packed codes + scale byte
 # Bytes crossing the L2's outward port per GEMM launch (mean of the three GEMMs), from the FETCH_SIZE and
 # WRITE_SIZE runs summarised in profiles/qkv_traffic_counters.md (FETCH_SIZE x 2.0 after calibration
 # against a 256 MiB copy)
-GEMM_TRAFFIC_BYTES = 260.0e6
+GEMM_TRAFFIC_BYTES = 267.7e6
 
 
 def event_time_ms(fn, iters, torch):

@@ -102,6 +102,20 @@ int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
                    int rounding, uint64_t seed, void *q_out, void *s_out, void *hip_stream);
 
 /*
+ * Both quantisations of one bf16 matrix from a single pass over it: the row-wise one a Fprop
+ * or Dgrad operand needs and the column-wise one the same tensor needs as a Dgrad or Wgrad
+ * operand (App. C.1-C.3; the transposed access is the costly layout of App. D).
+ *   x        bf16 [rows][ld], 16-byte aligned, ld % 8 == 0, rows % 32 == 0, cols % 32 == 0
+ *   q_last   uint8 [rows][cols/2], s_last uint8 [rows][cols/32]: exactly what mxfp4_quantize
+ *            writes for MXFP4_AXIS_LAST with the same hadamard, rounding and seed
+ *   q_first  uint8 [cols][rows/2], s_first uint8 [cols][rows/32]: the same for MXFP4_AXIS_FIRST
+ *   q_last, q_first 16-byte aligned.  rows == 0 or cols == 0 is a valid empty call.
+ */
+int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                        int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
+                        void *hip_stream);
+
+/*
  * Block-scaled FP4 GEMM on quantised operands (the MXFP4 GEMM that replaces the FP8 GEMM of
  * the linear layers, Sec. 1 and App. A.2):
  *     out[i][j] (+)= sum_c A[i][c] * B[j][c],  A = a_q/a_s [R_a][C],  B = b_q/b_s [R_b][C]
@@ -136,6 +150,30 @@ int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N
 int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw, int64_t M, int64_t N,
                      int64_t K, const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes,
                      void *hip_stream);
+
+/*
+ * Training pair with each tensor read once (Fig. 3: the same X and W feed Fprop and the two
+ * backward GEMMs).  mxfp4_linear_fwd_save computes Y as mxfp4_linear_fwd does and, from the
+ * same pass over X and W, also stores their column-wise quantisations W^T (for Dgrad) and
+ * X^T (for Wgrad) in `saved`; mxfp4_linear_bwd_saved then needs neither x nor w: it
+ * quantises dY both ways in one pass and runs Dgrad and Wgrad against `saved`.  Outputs are
+ * bit-identical to mxfp4_linear_fwd / mxfp4_linear_bwd with the same cfg.
+ *   saved: device buffer of at least mxfp4_linear_saved_bytes(M,N,K) bytes, 256-byte aligned,
+ *          owned by the caller, kept untouched between the two calls; offsets of q and s of
+ *          W^T (rows K, C=N) and X^T (rows K, C=M) from mxfp4_linear_saved_layout.
+ *   M % 32 == 0, N % 32 == 0, K % 32 == 0, all >= 1 (else MXFP4_ESHAPE).
+ *   workspace: as for mxfp4_linear_fwd (bwd = 0) and mxfp4_linear_bwd (bwd = 1).
+ *   dx or dw may be NULL to skip that GEMM.
+ */
+int mxfp4_linear_fwd_save(const void *x, const void *w, void *y, int64_t M, int64_t N, int64_t K,
+                          const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes, void *saved,
+                          size_t saved_bytes, void *hip_stream);
+int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes, void *dx, void *dw, int64_t M,
+                           int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+size_t mxfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K);
+/* offsets[4]: q, s of W^T then q, s of X^T inside `saved`.  Host-only. */
+int mxfp4_linear_saved_layout(int64_t M, int64_t N, int64_t K, size_t offsets[4]);
 
 /* Bytes of workspace the fused calls need (bwd = 0: forward, 1: backward).  Host-only. */
 size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd);

@@ -21,8 +21,10 @@ HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16 = 0, 1, 2, 3
 RNE, SR = 0, 1
 OUT_BF16, OUT_FP32 = 0, 1
 
-EXPORTS = ("mxfp4_quantize", "mxfp4_gemm", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
-           "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout", "mxfp4_status_string")
+EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_gemm", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
+           "mxfp4_linear_fwd_save", "mxfp4_linear_bwd_saved", "mxfp4_linear_saved_bytes",
+           "mxfp4_linear_saved_layout", "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout",
+           "mxfp4_status_string")
 
 
 class LinearCfg(ctypes.Structure):
@@ -52,6 +54,16 @@ def lib() -> ctypes.CDLL:
         vp, i64, ci, u64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint64, ctypes.c_size_t
         L.mxfp4_quantize.restype = ci
         L.mxfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, u64, vp, vp, vp]
+        L.mxfp4_quantize_dual.restype = ci
+        L.mxfp4_quantize_dual.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp, vp, vp]
+        L.mxfp4_linear_fwd_save.restype = ci
+        L.mxfp4_linear_fwd_save.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp, sz, vp]
+        L.mxfp4_linear_bwd_saved.restype = ci
+        L.mxfp4_linear_bwd_saved.argtypes = [vp, vp, sz, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
+        L.mxfp4_linear_saved_bytes.restype = sz
+        L.mxfp4_linear_saved_bytes.argtypes = [i64, i64, i64]
+        L.mxfp4_linear_saved_layout.restype = ci
+        L.mxfp4_linear_saved_layout.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
         L.mxfp4_gemm.restype = ci
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
         L.mxfp4_linear_fwd.restype = ci
@@ -109,6 +121,21 @@ def mxfp4_quantize(x, axis: int = AXIS_LAST, hadamard: int = HAD_NONE, rounding:
     _check("mxfp4_quantize", lib().mxfp4_quantize(_ptr(x), rows, cols, ld, axis, hadamard, rounding,
                                                   seed & (2**64 - 1), _ptr(q), _ptr(s), _stream_ptr(stream)))
     return q, s
+
+
+def mxfp4_quantize_dual(x, hadamard: int = HAD_NONE, rounding: int = RNE, seed: int = 0, stream=None):
+    """Both quantisations of x [rows][cols] from one pass: returns (q_last, s_last, q_first, s_first)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and (x.numel() == 0 or x.stride(1) == 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, x.stride(0))
+    u8 = dict(dtype=torch.uint8, device=x.device)
+    ql, sl = torch.empty((rows, cols // 2), **u8), torch.empty((rows, cols // 32), **u8)
+    qf, sf = torch.empty((cols, rows // 2), **u8), torch.empty((cols, rows // 32), **u8)
+    _check("mxfp4_quantize_dual", lib().mxfp4_quantize_dual(_ptr(x), rows, cols, ld, hadamard, rounding,
+                                                            seed & (2**64 - 1), _ptr(ql), _ptr(sl), _ptr(qf),
+                                                            _ptr(sf), _stream_ptr(stream)))
+    return ql, sl, qf, sf
 
 
 def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumulate: bool = False, stream=None):
@@ -175,4 +202,52 @@ def mxfp4_linear_bwd(dy, x, w, cfg: LinearCfg, dx=None, dw=None, need_dx: bool =
     _check("mxfp4_linear_bwd", lib().mxfp4_linear_bwd(_ptr(dy), _ptr(x), _ptr(w), _ptr(dx) if need_dx else None,
                                                       _ptr(dw) if need_dw else None, M, N, K, ctypes.byref(cfg),
                                                       _ptr(workspace), workspace.numel(), _stream_ptr(stream)))
+    return dx, dw, workspace
+
+
+def mxfp4_linear_saved_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().mxfp4_linear_saved_bytes(M, N, K))
+
+
+def mxfp4_linear_saved_layout(M: int, N: int, K: int):
+    arr = (ctypes.c_size_t * 4)()
+    _check("mxfp4_linear_saved_layout", lib().mxfp4_linear_saved_layout(M, N, K, arr))
+    return [int(v) for v in arr]
+
+
+def mxfp4_linear_fwd_save(x, w, cfg: LinearCfg, y=None, workspace=None, saved=None, stream=None):
+    """mxfp4_linear_fwd that also leaves the column-wise quantisations of W and X in `saved` for
+    mxfp4_linear_bwd_saved.  Returns (y, workspace, saved)."""
+    import torch
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and x.is_contiguous() and w.is_contiguous()
+    if workspace is None:
+        workspace = torch.empty(mxfp4_linear_workspace_bytes(M, N, K, cfg, False), dtype=torch.uint8, device=x.device)
+    if saved is None:
+        saved = torch.empty(mxfp4_linear_saved_bytes(M, N, K), dtype=torch.uint8, device=x.device)
+    if y is None:
+        y = torch.empty((M, N), dtype=_out_dtype(cfg.y_dtype), device=x.device)
+    _check("mxfp4_linear_fwd_save", lib().mxfp4_linear_fwd_save(
+        _ptr(x), _ptr(w), _ptr(y), M, N, K, ctypes.byref(cfg), _ptr(workspace), workspace.numel(), _ptr(saved),
+        saved.numel(), _stream_ptr(stream)))
+    return y, workspace, saved
+
+
+def mxfp4_linear_bwd_saved(dy, saved, K: int, cfg: LinearCfg, dx=None, dw=None, need_dx: bool = True,
+                           need_dw: bool = True, workspace=None, stream=None):
+    """Dgrad and Wgrad against the operands mxfp4_linear_fwd_save left in `saved`.  Returns (dx, dw, workspace)."""
+    import torch
+    M, N = dy.shape
+    assert dy.is_contiguous()
+    if workspace is None:
+        workspace = torch.empty(mxfp4_linear_workspace_bytes(M, N, K, cfg, True), dtype=torch.uint8, device=dy.device)
+    if need_dx and dx is None:
+        dx = torch.empty((M, K), dtype=_out_dtype(cfg.dx_dtype), device=dy.device)
+    if need_dw and dw is None:
+        assert not cfg.dw_accumulate, "accumulating into dW needs the caller's dW"
+        dw = torch.empty((N, K), dtype=_out_dtype(cfg.dw_dtype), device=dy.device)
+    _check("mxfp4_linear_bwd_saved", lib().mxfp4_linear_bwd_saved(
+        _ptr(dy), _ptr(saved), saved.numel(), _ptr(dx) if need_dx else None, _ptr(dw) if need_dw else None, M, N, K,
+        ctypes.byref(cfg), _ptr(workspace), workspace.numel(), _stream_ptr(stream)))
     return dx, dw, workspace

@@ -103,6 +103,21 @@ BwdLayout bwd_layout(int64_t M, int64_t N, int64_t K)
     return L;
 }
 
+struct SavedLayout {
+    size_t wtq, wts, xtq, xts, total;
+};
+SavedLayout saved_layout(int64_t M, int64_t N, int64_t K)
+{
+    SavedLayout L;
+    size_t o = 0;
+    L.wtq = o; o = round_up(o + (size_t)K * (N / 2), 256);
+    L.wts = o; o = round_up(o + (size_t)K * (N / 32), 256);
+    L.xtq = o; o = round_up(o + (size_t)K * (M / 2), 256);
+    L.xts = o; o = round_up(o + (size_t)K * (M / 32), 256);
+    L.total = o;
+    return L;
+}
+
 int check_cfg(const mxfp4_linear_cfg *cfg)
 {
     if (!cfg) return MXFP4_EINVAL;
@@ -144,6 +159,25 @@ int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
                 static_cast<uint8_t *>(q_out), static_cast<uint8_t *>(s_out)};
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e = (axis == MXFP4_AXIS_LAST) ? launch_quantize_rows(a, st) : launch_quantize_cols(a, st);
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
+int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                        int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
+                        void *hip_stream)
+{
+    // the union of the two single-axis argument rules
+    int rc = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_LAST, hadamard, rounding, q_last, s_last);
+    int rc2 = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_FIRST, hadamard, rounding, q_first, s_first);
+    if (rc > 0) return rc;
+    if (rc2 > 0) return rc2;
+    if (rc == 0 || rc2 == 0) return MXFP4_OK;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    QuantArgs a{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
+                static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
+    a.q_row = static_cast<uint8_t *>(q_last);
+    a.s_row = static_cast<uint8_t *>(s_last);
+    hipError_t e = launch_quantize_dual(a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
@@ -221,10 +255,18 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
         return MXFP4_EALIGN;
     if ((N % 8) != 0 || (K % 8) != 0) return MXFP4_EALIGN;  // dense bf16 rows must stay 16-byte aligned
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    if (dx) {
-        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq,
-                            ws + L.gs, hip_stream);
+    const bool dual = dx && dw && (N % 32) == 0;  // dY is needed both ways: read it once
+    if (dual) {
+        rc = mxfp4_quantize_dual(dy, M, N, N, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq, ws + L.gs,
+                                 ws + L.gtq, ws + L.gts, hip_stream);
         if (rc != MXFP4_OK) return rc;
+    }
+    if (dx) {
+        if (!dual) {
+            rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq,
+                                ws + L.gs, hip_stream);
+            if (rc != MXFP4_OK) return rc;
+        }
         rc = mxfp4_quantize(w, N, K, K, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.wtq,
                             ws + L.wts, hip_stream);
         if (rc != MXFP4_OK) return rc;
@@ -232,13 +274,93 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
         if (rc != MXFP4_OK) return rc;
     }
     if (dw) {
-        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gtq,
-                            ws + L.gts, hip_stream);
-        if (rc != MXFP4_OK) return rc;
+        if (!dual) {
+            rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gtq,
+                                ws + L.gts, hip_stream);
+            if (rc != MXFP4_OK) return rc;
+        }
         rc = mxfp4_quantize(x, M, K, K, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.xtq,
                             ws + L.xts, hip_stream);
         if (rc != MXFP4_OK) return rc;
         rc = mxfp4_gemm(ws + L.gtq, ws + L.gts, ws + L.xtq, ws + L.xts, N, K, M, dw, K, cfg->dw_dtype,
+                        cfg->dw_accumulate, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+    }
+    return MXFP4_OK;
+}
+
+size_t mxfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M < 0 || N < 0 || K < 0) return 0;
+    return saved_layout(M, N, K).total;
+}
+
+int mxfp4_linear_saved_layout(int64_t M, int64_t N, int64_t K, size_t offsets[4])
+{
+    if (!offsets || M < 0 || N < 0 || K < 0) return MXFP4_EINVAL;
+    const SavedLayout L = saved_layout(M, N, K);
+    const size_t o[4] = {L.wtq, L.wts, L.xtq, L.xts};
+    memcpy(offsets, o, sizeof(o));
+    return MXFP4_OK;
+}
+
+int mxfp4_linear_fwd_save(const void *x, const void *w, void *y, int64_t M, int64_t N, int64_t K,
+                          const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes, void *saved,
+                          size_t saved_bytes, void *hip_stream)
+{
+    int rc = check_cfg(cfg);
+    if (rc != MXFP4_OK) return rc;
+    if (M <= 0 || N <= 0 || K <= 0 || (M % 32) != 0 || (N % 32) != 0 || (K % 32) != 0) return MXFP4_ESHAPE;
+    if (!x || !w || !y || !workspace || !saved) return MXFP4_EINVAL;
+    const FwdLayout L = fwd_layout(M, N, K);
+    const SavedLayout S = saved_layout(M, N, K);
+    if (workspace_bytes < L.total || saved_bytes < S.total) return MXFP4_EWORKSPACE;
+    if (!aligned(workspace, 256) || !aligned(saved, 256) || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16))
+        return MXFP4_EALIGN;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    uint8_t *sv = static_cast<uint8_t *>(saved);
+    rc = mxfp4_quantize_dual(x, M, K, K, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.xq, ws + L.xs, sv + S.xtq,
+                             sv + S.xts, hip_stream);
+    if (rc != MXFP4_OK) return rc;
+    rc = mxfp4_quantize_dual(w, N, K, K, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.wq, ws + L.ws, sv + S.wtq,
+                             sv + S.wts, hip_stream);
+    if (rc != MXFP4_OK) return rc;
+    return mxfp4_gemm(ws + L.xq, ws + L.xs, ws + L.wq, ws + L.ws, M, N, K, y, N, cfg->y_dtype, 0, hip_stream);
+}
+
+int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes, void *dx, void *dw, int64_t M,
+                           int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_cfg(cfg);
+    if (rc != MXFP4_OK) return rc;
+    if (M <= 0 || N <= 0 || K <= 0 || (M % 32) != 0 || (N % 32) != 0 || (K % 32) != 0) return MXFP4_ESHAPE;
+    if (!dx && !dw) return MXFP4_OK;
+    if (!dy || !saved || !workspace) return MXFP4_EINVAL;
+    const BwdLayout L = bwd_layout(M, N, K);
+    const SavedLayout S = saved_layout(M, N, K);
+    if (workspace_bytes < L.total || saved_bytes < S.total) return MXFP4_EWORKSPACE;
+    if (!aligned(workspace, 256) || !aligned(saved, 256) || !aligned(dy, 16) || (dx && !aligned(dx, 16)) ||
+        (dw && !aligned(dw, 16)))
+        return MXFP4_EALIGN;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const uint8_t *sv = static_cast<const uint8_t *>(saved);
+    if (dx && dw)
+        rc = mxfp4_quantize_dual(dy, M, N, N, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq, ws + L.gs,
+                                 ws + L.gtq, ws + L.gts, hip_stream);
+    else if (dx)
+        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq,
+                            ws + L.gs, hip_stream);
+    else
+        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gtq,
+                            ws + L.gts, hip_stream);
+    if (rc != MXFP4_OK) return rc;
+    if (dx) {
+        rc = mxfp4_gemm(ws + L.gq, ws + L.gs, sv + S.wtq, sv + S.wts, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+    }
+    if (dw) {
+        rc = mxfp4_gemm(ws + L.gtq, ws + L.gts, sv + S.xtq, sv + S.xts, N, K, M, dw, K, cfg->dw_dtype,
                         cfg->dw_accumulate, hip_stream);
         if (rc != MXFP4_OK) return rc;
     }

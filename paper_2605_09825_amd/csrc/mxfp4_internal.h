@@ -13,12 +13,15 @@ struct QuantArgs {
     int hadamard, rounding;
     uint64_t seed;
     uint8_t *q, *s;
+    uint8_t *q_row = nullptr, *s_row = nullptr;  // launch_quantize_dual only: the row-wise outputs
 };
 
 // blocks along rows (1x32): q[rows][cols/2], s[rows][cols/32]
 hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st);
 // blocks down columns (32x1): q[cols][rows/2], s[cols][rows/32]
 hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st);
+// both from one pass over x: q, s as launch_quantize_cols; q_row, s_row as launch_quantize_rows
+hipError_t launch_quantize_dual(const QuantArgs &a, hipStream_t st);
 
 struct GemmArgs {
     const uint8_t *aq, *as, *bq, *bs;

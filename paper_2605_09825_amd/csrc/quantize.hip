@@ -14,6 +14,9 @@
 //     256 contiguous bytes per wave and row); the eight waves of a workgroup take
 //     eight consecutive row blocks, and the packed codes are regrouped through LDS
 //     so that each output row receives 128 contiguous bytes.
+//   * both at once: the column-wise workgroup tile, whose 256 x 128 elements are also
+//     parked in LDS and read back as row-wise blocks; memory delivers the tensor once
+//     for the two outputs.
 #include "mxfp4_internal.h"
 
 namespace mxfp4 {
@@ -105,13 +108,19 @@ __device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask,
         for (int i = 0; i < 32; ++i) v[i] = v[i] * 0.25f;
     }
 
-    // block maximum on the bit patterns: NaN and infinity compare above every finite value
-    uint32_t amax = 0;
+    // block maximum on the bit patterns (NaN and infinity compare above every finite value), without
+    // clearing 32 sign bits: the unsigned maximum is the largest-magnitude negative value if there is
+    // one, the signed maximum (from 0) the largest positive one
+    uint32_t mu = 0;
+    int32_t mi = 0;
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
-        uint32_t b = __float_as_uint(v[i]) & 0x7FFFFFFFu;
-        amax = b > amax ? b : amax;
+        const uint32_t b = __float_as_uint(v[i]);
+        mu = b > mu ? b : mu;
+        mi = (int32_t)b > mi ? (int32_t)b : mi;
     }
+    mu &= 0x7FFFFFFFu;
+    const uint32_t amax = (uint32_t)mi > mu ? (uint32_t)mi : mu;
     uint32_t eb = amax >> 23;
     bool bad = (eb == 255u);
     uint32_t sb = eb > 2u ? eb - 2u : 0u;  // eb <= 254 here, so sb <= 252
@@ -151,6 +160,22 @@ __device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask,
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// 32 contiguous bf16 (four 16-byte words) widened to fp32
+__device__ __forceinline__ void widen(const uint4 (&raw)[4], float (&v)[32])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        v[8 * j + 0] = bf16_lo(raw[j].x);
+        v[8 * j + 1] = bf16_hi(raw[j].x);
+        v[8 * j + 2] = bf16_lo(raw[j].y);
+        v[8 * j + 3] = bf16_hi(raw[j].y);
+        v[8 * j + 4] = bf16_lo(raw[j].z);
+        v[8 * j + 5] = bf16_hi(raw[j].z);
+        v[8 * j + 6] = bf16_lo(raw[j].w);
+        v[8 * j + 7] = bf16_hi(raw[j].w);
+    }
+}
+
 // ---- row-wise (1x32) ---------------------------------------------------------------------
 // One lane per block.  nblocks = rows * (cols/32); block g is row g / bpr, column block g % bpr.
 template <int HAD, int RND>
@@ -173,17 +198,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
 #pragma unroll
     for (int j = 0; j < 4; ++j) raw[j] = p[j];
     float v[32];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        v[8 * j + 0] = bf16_lo(raw[j].x);
-        v[8 * j + 1] = bf16_hi(raw[j].x);
-        v[8 * j + 2] = bf16_lo(raw[j].y);
-        v[8 * j + 3] = bf16_hi(raw[j].y);
-        v[8 * j + 4] = bf16_lo(raw[j].z);
-        v[8 * j + 5] = bf16_hi(raw[j].z);
-        v[8 * j + 6] = bf16_lo(raw[j].w);
-        v[8 * j + 7] = bf16_hi(raw[j].w);
-    }
+    widen(raw, v);
     uint4 codes;
     uint32_t sb;
     encode_block<HAD, RND>(v, sign_mask, key, (uint64_t)g * 32u, codes, sb);
@@ -195,15 +210,28 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
 // Workgroup tile: 256 rows (8 row blocks, one per wave) x 128 columns (2 per lane).
 constexpr int CT_COLS = 128, CT_RB = 8;
 
-template <int HAD, int RND>
+// DUAL: additionally emit the row-wise quantisation q_row[rows][cols/2], s_row[rows][cols/32] of the same
+// tile (needs cols % 32 == 0).  Each wave parks its 32 x 128 elements in LDS and reads them back as 128
+// row blocks, two per lane, four lanes per row, so the tensor is fetched from memory once.  The parked
+// tile and the regrouping buffers of the column-wise output share the same LDS.
+constexpr int RAW_PITCH = 272;  // bytes per parked row: 256 + 16, so that the 16-byte reads below (16 lanes =
+                                // 4 rows x 4 blocks per issue) and the dword writes touch every bank once
+constexpr int LDS_Q_BYTES = CT_RB * (CT_COLS + 1) * 16, LDS_S_BYTES = CT_COLS * CT_RB;
+constexpr int LDS_RAW_BYTES = CT_RB * 32 * RAW_PITCH;
+
+template <int HAD, int RND, bool DUAL>
 __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t rows,
                                                             int64_t cols, int64_t ld, uint32_t sign_mask,
                                                             RngKey key, uint8_t *__restrict__ q,
                                                             uint8_t *__restrict__ s, int s_vec8,
-                                                            uint32_t col_groups)
+                                                            uint32_t col_groups, uint8_t *__restrict__ q_row,
+                                                            uint8_t *__restrict__ s_row, int s_row_vec4)
 {
-    __shared__ uint4 lds_q[CT_RB][CT_COLS + 1];
-    __shared__ __attribute__((aligned(8))) uint8_t lds_s[CT_COLS][CT_RB];
+    constexpr int LDS_BYTES = (DUAL && LDS_RAW_BYTES > LDS_Q_BYTES + LDS_S_BYTES) ? LDS_RAW_BYTES
+                                                                                  : LDS_Q_BYTES + LDS_S_BYTES;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
+    uint4(*lds_q)[CT_COLS + 1] = reinterpret_cast<uint4(*)[CT_COLS + 1]>(lds);
+    uint8_t(*lds_s)[CT_RB] = reinterpret_cast<uint8_t(*)[CT_RB]>(lds + LDS_Q_BYTES);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t by = blockIdx.x / col_groups, bx = blockIdx.x - by * col_groups;
@@ -223,6 +251,45 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
 #pragma unroll
         for (int i = 0; i < 32; ++i) raw[i] = 0;
     }
+
+    if (DUAL) {
+        uint8_t *mine = lds + w * (32 * RAW_PITCH);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) *reinterpret_cast<uint32_t *>(mine + i * RAW_PITCH + 4 * lane) = raw[i];
+        __syncthreads();
+        const int cb = lane & 3;
+        const int64_t colb = c0 + 32 * cb;
+        const int64_t bpr = cols >> 5;
+        const bool on = (rb < nrb) && (colb < cols);
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int r = (lane >> 2) + 16 * pass;
+            const int64_t row = rb * 32 + r;
+            const uint4 *p = reinterpret_cast<const uint4 *>(mine + r * RAW_PITCH + 64 * cb);
+            uint4 rraw[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rraw[j] = p[j];
+            float v[32];
+            widen(rraw, v);
+            uint4 codes;
+            uint32_t sb;
+            encode_block<HAD, RND>(v, sign_mask, key, (uint64_t)row * (uint64_t)cols + (uint64_t)colb, codes, sb);
+            const int64_t g = row * bpr + (colb >> 5);
+            if (on) reinterpret_cast<uint4 *>(q_row)[g] = codes;
+            // the four scale bytes of one row of the tile go out as one dword where they can
+            uint32_t s4 = sb;
+            s4 |= (uint32_t)__shfl_down((int)sb, 1) << 8;
+            s4 |= (uint32_t)__shfl_down((int)sb, 2) << 16;
+            s4 |= (uint32_t)__shfl_down((int)sb, 3) << 24;
+            if (s_row_vec4 && c0 + CT_COLS <= cols) {
+                if (on && cb == 0) *reinterpret_cast<uint32_t *>(s_row + g) = s4;
+            } else if (on) {
+                s_row[g] = (uint8_t)sb;
+            }
+        }
+        __syncthreads();  // every wave is done with the parked tile: its LDS becomes the regrouping buffers
+    }
+
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         float v[32];
@@ -274,7 +341,7 @@ hipError_t launch_rows_h(const QuantArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int HAD>
+template <int HAD, bool DUAL>
 hipError_t launch_cols_h(const QuantArgs &a, hipStream_t st)
 {
     const int64_t nrb = a.rows / 32;
@@ -284,12 +351,13 @@ hipError_t launch_cols_h(const QuantArgs &a, hipStream_t st)
     const RngKey key = make_key(a.seed);
     const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
     const int s_vec8 = ((nrb % 8) == 0) && ((reinterpret_cast<uintptr_t>(a.s) % 8) == 0);
+    const int s_row_vec4 = DUAL && (((a.cols / 32) % 4) == 0) && ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
     if (a.rounding == RND_RNE)
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols, a.ld,
-                           sign_mask, key, a.q, a.s, s_vec8, col_groups);
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, DUAL>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
+                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4);
     else
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR>), grid, dim3(512), 0, st, a.x, a.rows, a.cols, a.ld,
-                           sign_mask, key, a.q, a.s, s_vec8, col_groups);
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, DUAL>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
+                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4);
     return hipGetLastError();
 }
 
@@ -308,10 +376,20 @@ hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st)
 hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st)
 {
     switch (a.hadamard) {
-        case HAD_NONE: return launch_cols_h<HAD_NONE>(a, st);
-        case HAD_DET: return launch_cols_h<HAD_DET>(a, st);
-        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN>(a, st);
-        default: return launch_cols_h<HAD_DET16>(a, st);
+        case HAD_NONE: return launch_cols_h<HAD_NONE, false>(a, st);
+        case HAD_DET: return launch_cols_h<HAD_DET, false>(a, st);
+        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, false>(a, st);
+        default: return launch_cols_h<HAD_DET16, false>(a, st);
+    }
+}
+
+hipError_t launch_quantize_dual(const QuantArgs &a, hipStream_t st)
+{
+    switch (a.hadamard) {
+        case HAD_NONE: return launch_cols_h<HAD_NONE, true>(a, st);
+        case HAD_DET: return launch_cols_h<HAD_DET, true>(a, st);
+        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, true>(a, st);
+        default: return launch_cols_h<HAD_DET16, true>(a, st);
     }
 }
 

@@ -107,6 +107,42 @@ def test_linear_argument_errors_and_workspace(L):
     assert b(P, P, P, None, None, M, N, K, c, W, need_b, None) == mx.OK   # nothing asked
 
 
+def test_dual_and_saved_argument_errors(L):
+    d = L.mxfp4_quantize_dual
+    assert d(P, 64, 64, 64, 9, 0, 0, P, P, P, P, None) == mx.EINVAL       # hadamard
+    assert d(P, 64, 64, 64, 0, 0, 0, P, P, None, P, None) == mx.EINVAL
+    assert d(P, 64, 64, 64, 0, 0, 0, None, P, P, P, None) == mx.EINVAL
+    assert d(P, 48, 64, 64, 0, 0, 0, P, P, P, P, None) == mx.ESHAPE       # rows % 32
+    assert d(P, 64, 48, 48, 0, 0, 0, P, P, P, P, None) == mx.ESHAPE       # cols % 32
+    assert d(P, 64, 64, 68, 0, 0, 0, P, P, P, P, None) == mx.EALIGN       # ld % 8
+    assert d(P + 4, 64, 64, 64, 0, 0, 0, P, P, P, P, None) == mx.EALIGN
+    assert d(P, 64, 64, 64, 0, 0, 0, P, P, P + 8, P, None) == mx.EALIGN
+    assert d(None, 64, 0, 64, 0, 0, 0, None, None, None, None, None) == mx.OK  # empty
+    cfg = mx.make_cfg()
+    c = ctypes.byref(cfg)
+    M, N, K = 64, 96, 128
+    need_f = mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, False)
+    need_b = mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, True)
+    need_s = mx.mxfp4_linear_saved_bytes(M, N, K)
+    assert need_s >= K * (N // 2 + N // 32) + K * (M // 2 + M // 32)
+    off = mx.mxfp4_linear_saved_layout(M, N, K)
+    assert off == sorted(off) and all(o % 256 == 0 for o in off) and off[-1] + K * (M // 32) <= need_s
+    W, S = 0x100000, 0x200000
+    f, b = L.mxfp4_linear_fwd_save, L.mxfp4_linear_bwd_saved
+    assert f(P, P, P, M, N, K, c, W, need_f, S, need_s - 1, None) == mx.EWORKSPACE
+    assert f(P, P, P, M, N, K, c, W, need_f - 1, S, need_s, None) == mx.EWORKSPACE
+    assert f(P, P, P, 48, N, K, c, W, need_f, S, need_s, None) == mx.ESHAPE   # M % 32
+    assert f(P, P, P, M, 100, K, c, W, need_f, S, need_s, None) == mx.ESHAPE  # N % 32
+    assert f(P, P, P, M, N, K, c, W, need_f, None, need_s, None) == mx.EINVAL
+    assert f(P, P, P, M, N, K, c, W, need_f, S + 16, need_s, None) == mx.EALIGN
+    assert b(P, S, need_s - 1, P, P, M, N, K, c, W, need_b, None) == mx.EWORKSPACE
+    assert b(P, S, need_s, P, P, M, N, K, c, W, need_b - 1, None) == mx.EWORKSPACE
+    assert b(P, None, need_s, P, P, M, N, K, c, W, need_b, None) == mx.EINVAL
+    assert b(None, S, need_s, P, P, M, N, K, c, W, need_b, None) == mx.EINVAL
+    assert b(P, S, need_s, P, P, M, N, 100, c, W, need_b, None) == mx.ESHAPE
+    assert b(P, S, need_s, None, None, M, N, K, c, W, need_b, None) == mx.OK  # nothing asked
+
+
 def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
     monkeypatch.setattr(mx, "_lib", None)
     monkeypatch.setattr(mx, "LIB_PATH", str(tmp_path / "nope.so"))

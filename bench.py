@@ -4,8 +4,11 @@
 One "step" is one pass of the whole path over one batch of synthetic input: for the
 Llama-3.1-8B fused QKV projection (M=8192 tokens, K=4096, N=6144) the three training GEMMs
 Fprop, Dgrad and Wgrad, each preceded by the deterministic 32-point Hadamard rotation and the
-MXFP4 quantisation of both operands (6 quantiser launches + 3 GEMM launches per step).
-Inputs are resident in HBM before the timed region starts.
+MXFP4 quantisation of both operands.  The timed step is the training pair mxfp4_linear_fwd_save +
+mxfp4_linear_bwd_saved: X, W and dY are each read once and quantised along both axes (3 quantiser
+launches producing the 6 quantised operands, then 3 GEMM launches).  The same work through
+mxfp4_linear_fwd + mxfp4_linear_bwd (5 quantiser launches) is timed as well and reported as
+`separate_calls_ms_per_step`.  Inputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` = 3 * 2*M*N*K flop / step time, i.e. GEMM TFLOP/s including the
 rotation and quantisation time.  `roofline` describes the dominant kernel (the FP4 GEMM)
@@ -28,6 +31,7 @@ M, K, N = 8192, 4096, 6144
 PEAK_FP4_TFLOPS = 10100.0  # MI355X dense MXFP4 MFMA peak
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 BYTES_PER_ELEM = 2.0 + 0.5 + 1.0 / 32.0  # bf16 read + packed codes + scale byte per element
+BYTES_PER_ELEM_DUAL = 2.0 + 2 * (0.5 + 1.0 / 32.0)  # one read, both quantisations written
 
 # Bytes crossing the L2's outward port per GEMM launch (mean of the three GEMMs), from the FETCH_SIZE and
 # WRITE_SIZE runs summarised in profiles/qkv_traffic_counters.md (FETCH_SIZE x 2.0 after calibration
@@ -50,12 +54,13 @@ def event_time_ms(fn, iters, torch):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--counter-run", action="store_true",
-                    help="for rocprofv3 --pmc: one 256 MiB device copy (known traffic) followed by two "
-                         "steps of the workload, no timing, no JSON")
+                    help="for rocprofv3 --pmc: one 256 MiB device copy (known traffic) followed by one "
+                         "step through the training pair and one through the separate calls, no timing, "
+                         "no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1",
@@ -85,7 +90,13 @@ def main() -> int:
     dx = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
     dw = torch.empty((N, K), dtype=torch.float32, device=dev)
 
+    saved = torch.empty(mx.mxfp4_linear_saved_bytes(M, N, K), dtype=torch.uint8, device=dev)
+
     def step():
+        mx.mxfp4_linear_fwd_save(x, w, cfg, y=y, workspace=ws_f, saved=saved)
+        mx.mxfp4_linear_bwd_saved(dy, saved, K, cfg, dx=dx, dw=dw, workspace=ws_b)
+
+    def step_separate():
         mx.mxfp4_linear_fwd(x, w, cfg, y=y, workspace=ws_f)
         mx.mxfp4_linear_bwd(dy, x, w, cfg, dx=dx, dw=dw, workspace=ws_b)
 
@@ -96,7 +107,7 @@ def main() -> int:
         torch.cuda.synchronize()
         dst.copy_(ref)  # reference dispatch: reads 256 MiB, writes 256 MiB
         step()
-        step()
+        step_separate()
         torch.cuda.synchronize()
         print("counter run done: reference copy 268435456 bytes each way, then 2 steps")
         return 0
@@ -110,10 +121,19 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    for _ in range(2):
+        step_separate()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_separate()
+    torch.cuda.synchronize()
+    ms_separate = (time.perf_counter() - t0) * 1e3 / args.steps
     flop_step = 3 * 2.0 * M * N * K
     tflops_incl = flop_step / (ms_per_step * 1e-3) / 1e12
 
     # ---- per-kernel durations, live, with events on the launch stream -------------------------
+    # (torch's current stream is the stream every call above was launched on)
     off_f = mx.mxfp4_linear_workspace_layout(M, N, K, False)
     off_b = mx.mxfp4_linear_workspace_layout(M, N, K, True)
 
@@ -128,12 +148,11 @@ def main() -> int:
     wtq, wts = view(ws_b, off_b, K, N, 1)
     gtq, gts = view(ws_b, off_b, N, M, 2)
     xtq, xts = view(ws_b, off_b, K, M, 3)
-    iters = max(5, args.steps)
-    t_fprop = event_time_ms(lambda: mx.mxfp4_gemm(xq, xs, wq, wsc, out=y, out_dtype=mx.OUT_BF16), iters, torch)
-    t_dgrad = event_time_ms(lambda: mx.mxfp4_gemm(gq, gs, wtq, wts, out=dx, out_dtype=mx.OUT_BF16), iters, torch)
-    t_wgrad = event_time_ms(lambda: mx.mxfp4_gemm(gtq, gts, xtq, xts, out=dw, out_dtype=mx.OUT_FP32), iters, torch)
-    t_gemm = (t_fprop + t_dgrad + t_wgrad) / 3.0
-    gemm_tflops = 2.0 * M * N * K / (t_gemm * 1e-3) / 1e12
+    off_s = mx.mxfp4_linear_saved_layout(M, N, K)
+    sv_wtq = saved[off_s[0]: off_s[0] + K * N // 2].view(K, N // 2)
+    sv_wts = saved[off_s[1]: off_s[1] + K * N // 32].view(K, N // 32)
+    sv_xtq = saved[off_s[2]: off_s[2] + K * M // 2].view(K, M // 2)
+    sv_xts = saved[off_s[3]: off_s[3] + K * M // 32].view(K, M // 32)
 
     def q_rows(t, q, s):
         mx.mxfp4_quantize(t, mx.AXIS_LAST, mx.HAD_DET, mx.RNE, 0, q=q, s=s)
@@ -141,6 +160,51 @@ def main() -> int:
     def q_cols(t, q, s):
         mx.mxfp4_quantize(t, mx.AXIS_FIRST, mx.HAD_DET, mx.RNE, 0, q=q, s=s)
 
+    L = mx.lib()
+    st = torch.cuda.current_stream().cuda_stream
+
+    def q_dual(t, ql, sl, qf, sf):
+        rc = L.mxfp4_quantize_dual(t.data_ptr(), t.shape[0], t.shape[1], t.shape[1], mx.HAD_DET, mx.RNE, 0,
+                                   ql.data_ptr(), sl.data_ptr(), qf.data_ptr(), sf.data_ptr(), st)
+        assert rc == mx.OK
+
+    # The launches of one step, in the step's order and on the step's buffers, issued through the single-operation
+    # entry points so that an event pair can bracket every kernel: a second timed region of the same work.
+    launches = [
+        ("x_dual", lambda: q_dual(x, xq, xs, sv_xtq, sv_xts)),
+        ("w_dual", lambda: q_dual(w, wq, wsc, sv_wtq, sv_wts)),
+        ("fprop", lambda: mx.mxfp4_gemm(xq, xs, wq, wsc, out=y, out_dtype=mx.OUT_BF16)),
+        ("dy_dual", lambda: q_dual(dy, gq, gs, gtq, gts)),
+        ("dgrad", lambda: mx.mxfp4_gemm(gq, gs, sv_wtq, sv_wts, out=dx, out_dtype=mx.OUT_BF16)),
+        ("wgrad", lambda: mx.mxfp4_gemm(gtq, gts, sv_xtq, sv_xts, out=dw, out_dtype=mx.OUT_FP32)),
+    ]
+    n_inst = min(args.steps, 100)
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in launches]
+          for _ in range(n_inst)]
+    for _ in range(3):
+        for _, fn in launches:
+            fn()
+    torch.cuda.synchronize()
+    for i in range(n_inst):
+        for k, (_, fn) in enumerate(launches):
+            ev[i][k][0].record()
+            fn()
+            ev[i][k][1].record()
+    torch.cuda.synchronize()
+    t_k = {name: sum(ev[i][k][0].elapsed_time(ev[i][k][1]) for i in range(n_inst)) / n_inst
+           for k, (name, _) in enumerate(launches)}
+    # Each bracket also holds the dispatch gap to the previous kernel (the event records serialise the queue), so
+    # the kernel's own duration is taken from back-to-back launches of the same GEMM on the same operands, which
+    # is what a kernel trace reports as well; both are printed.
+    iters = min(max(5, args.steps), 50)
+    t_fprop = event_time_ms(launches[2][1], iters, torch)
+    t_dgrad = event_time_ms(launches[4][1], iters, torch)
+    t_wgrad = event_time_ms(launches[5][1], iters, torch)
+    t_gemm = (t_fprop + t_dgrad + t_wgrad) / 3.0
+    gemm_tflops = 2.0 * M * N * K / (t_gemm * 1e-3) / 1e12
+    t_quant_total = t_k["x_dual"] + t_k["w_dual"] + t_k["dy_dual"]
+
+    # the single-axis kernels on the same (cache-warm) operands, back to back
     t_q = {
         "x_rows": event_time_ms(lambda: q_rows(x, xq, xs), iters, torch),
         "w_rows": event_time_ms(lambda: q_rows(w, wq, wsc), iters, torch),
@@ -150,7 +214,7 @@ def main() -> int:
         "x_cols": event_time_ms(lambda: q_cols(x, xtq, xts), iters, torch),
     }
     elems = {"x_rows": M * K, "w_rows": N * K, "dy_rows": M * N, "w_cols": N * K, "dy_cols": M * N, "x_cols": M * K}
-    t_quant_total = sum(t_q.values())
+    t_q.update({k: t_k[k] for k in ("x_dual", "w_dual", "dy_dual")})
 
     # HBM-resident rate: rotate over 10 distinct X-sized inputs (640 MiB > the 256 MB last-level cache)
     rot = [x] + [torch.empty_like(x).copy_(x) for _ in range(9)]
@@ -162,14 +226,21 @@ def main() -> int:
             state["i"] += 1
         return run
 
+    def dual_rot():
+        q_dual(rot[state["i"] % len(rot)], xq, xs, xtq, xts)
+        state["i"] += 1
+
     n_rot = 2 * len(rot)
     q_rot(q_rows)()
     q_rot(q_cols)()
+    dual_rot()
     t_rows_cold = event_time_ms(q_rot(q_rows), n_rot, torch)
     t_cols_cold = event_time_ms(q_rot(q_cols), n_rot, torch)
+    t_dual_cold = event_time_ms(dual_rot, n_rot, torch)
     del rot
-    gbs = lambda n_el, ms: n_el * BYTES_PER_ELEM / (ms * 1e-3) / 1e9
+    gbs = lambda n_el, ms, bpe=BYTES_PER_ELEM: n_el * bpe / (ms * 1e-3) / 1e9
     quant_rows_gbs, quant_cols_gbs = gbs(M * K, t_rows_cold), gbs(M * K, t_cols_cold)
+    quant_dual_gbs = gbs(M * K, t_dual_cold, BYTES_PER_ELEM_DUAL)
 
     out = {
         "metric": "mxfp4_linear_gemm_tflops_incl_hadamard_quantize",
@@ -187,8 +258,10 @@ def main() -> int:
         "config": {
             "workload": "Llama-3.1-8B fused QKV linear, Fprop+Dgrad+Wgrad, M=8192 K=4096 N=6144, "
                         "deterministic H32 + MXFP4 RNE on both operands of each GEMM; y,dx bf16, dw fp32",
-            "M": M, "K": K, "N": N, "launches_per_step": 9,
+            "M": M, "K": K, "N": N, "launches_per_step": 6,
+            "calls": "mxfp4_linear_fwd_save + mxfp4_linear_bwd_saved",
         },
+        "separate_calls_ms_per_step": round(ms_separate, 4),
         "pct_of_fp4_peak_incl_quant": round(100.0 * tflops_incl / PEAK_FP4_TFLOPS, 2),
         "roofline": {
             "kernel": "mxfp4 gemm (mean of fprop, dgrad, wgrad launches)",
@@ -199,6 +272,7 @@ def main() -> int:
             "frac": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
             "traffic": GEMM_TRAFFIC_BYTES,
             "launch_ms": {"fprop": round(t_fprop, 4), "dgrad": round(t_dgrad, 4), "wgrad": round(t_wgrad, 4)},
+            "in_step_bracket_ms": {k: round(t_k[k], 4) for k in ("fprop", "dgrad", "wgrad")},
         },
         "quantizer": {
             "bound": "hbm",
@@ -209,10 +283,14 @@ def main() -> int:
                                   "launch_ms": round(t_rows_cold, 4)},
             "cols_hbm_resident": {"achieved": round(quant_cols_gbs, 1), "frac": round(quant_cols_gbs / PEAK_HBM_GBS, 4),
                                   "launch_ms": round(t_cols_cold, 4)},
+            "dual_hbm_resident": {"achieved": round(quant_dual_gbs, 1), "frac": round(quant_dual_gbs / PEAK_HBM_GBS, 4),
+                                  "launch_ms": round(t_dual_cold, 4), "bytes_per_element": BYTES_PER_ELEM_DUAL},
             "in_step_ms": {k: round(v, 4) for k, v in t_q.items()},
-            "in_step_gbs_cache_warm": {k: round(gbs(elems[k], v), 1) for k, v in t_q.items()},
+            "in_step_gbs_cache_warm": {k: round(gbs(elems[k], t_q[k]), 1) for k in elems},
         },
-        "breakdown_ms": {"gemm_total": round(3 * t_gemm, 4), "quantize_total": round(t_quant_total, 4)},
+        "breakdown_ms": {"gemm_total": round(t_k["fprop"] + t_k["dgrad"] + t_k["wgrad"], 4),
+                         "quantize_total": round(t_quant_total, 4),
+                         "note": "event brackets inside a second timed region; each includes the dispatch gap"},
     }
 
     if not args.no_cpu_baseline:

@@ -67,6 +67,9 @@ def lib() -> ctypes.CDLL:
         L.orc_quantize.restype = ctypes.c_int
         L.orc_quantize.argtypes = [u16p, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                    ctypes.c_uint64, u8p, u8p]
+        L.orc_quantize_2d.restype = ctypes.c_int
+        L.orc_quantize_2d.argtypes = [u16p, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_uint64, u8p, u8p]
         L.orc_dequantize.restype = None
         L.orc_dequantize.argtypes = [u8p, u8p, i64, i64, f64p]
         L.orc_gemm.restype = ctypes.c_int
@@ -151,6 +154,25 @@ def quantize(x_bf16: np.ndarray, axis: int = AXIS_LAST, had: int = HAD_NONE, rnd
                             seed & (2**64 - 1), _p(q, ctypes.c_uint8), _p(s, ctypes.c_uint8))
     if rc != 0:
         raise RuntimeError(f"orc_quantize failed: {rc}")
+    return q, s
+
+
+def quantize_2d(x_bf16: np.ndarray, axis: int = AXIS_LAST, had: int = HAD_NONE, rnd: int = RNE,
+                seed: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """As quantize(), with one scale per 32 x 32 region (orc_quantize_2d)."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2
+    assert x_bf16.strides[1] == 2 and x_bf16.strides[0] % 2 == 0
+    rows, cols = x_bf16.shape
+    ld = x_bf16.strides[0] // 2
+    R, C = (rows, cols) if axis == AXIS_LAST else (cols, rows)
+    if C % 32 != 0 or R % 32 != 0:
+        raise ValueError("both lengths must be multiples of 32")
+    q = np.empty((R, C // 2), dtype=np.uint8)
+    s = np.empty((R, C // 32), dtype=np.uint8)
+    rc = lib().orc_quantize_2d(_p(x_bf16, ctypes.c_uint16), rows, cols, ld, axis, had, rnd,
+                               seed & (2**64 - 1), _p(q, ctypes.c_uint8), _p(s, ctypes.c_uint8))
+    if rc != 0:
+        raise RuntimeError(f"orc_quantize_2d failed: {rc}")
     return q, s
 
 

@@ -187,10 +187,8 @@ void orc_wht(float *v, int n)
 /* The block quantiser                                                        */
 /* ------------------------------------------------------------------------- */
 
-/* v[0..31]: the block, widened to fp32, in order along the contraction axis.
- * idx0: linear index of element 0 of the block in the quantised output. */
-static void quantize_block(float *v, int had, int rnd, uint64_t seed, uint32_t sign_mask,
-                           uint64_t idx0, uint8_t *codes, uint8_t *scale_byte)
+/* Optional sign flips and rotation of one block v[0..31] (App. A.2), in place. */
+static void rotate_block(float *v, int had, uint32_t sign_mask)
 {
     if (had == ORC_HAD_RANDSIGN)
         for (int i = 0; i < MX_BLOCK; ++i)
@@ -213,14 +211,23 @@ static void quantize_block(float *v, int had, int rnd, uint64_t seed, uint32_t s
             v[i] = p;
         }
     }
+}
 
+/* Largest magnitude of n values as an fp32 bit pattern (NaN and infinity
+ * compare above every finite value). */
+static uint32_t amax_bits_of(const float *v, int n)
+{
     uint32_t amax_bits = 0;
-    for (int i = 0; i < MX_BLOCK; ++i) {
+    for (int i = 0; i < n; ++i) {
         uint32_t b = f32_bits(v[i]) & 0x7FFFFFFFu;
         if (b > amax_bits) amax_bits = b;
     }
-    unsigned sb = orc_e8m0_from_amax_bits(amax_bits);
-    *scale_byte = (uint8_t)sb;
+    return amax_bits;
+}
+
+/* FP4 codes of one rotated block under the shared scale byte sb (eq. (1)). */
+static void encode_block(const float *v, unsigned sb, int rnd, uint64_t seed, uint64_t idx0, uint8_t *codes)
+{
     if (sb == 0xFFu) {
         memset(codes, 0, MX_BLOCK);
         return;
@@ -231,6 +238,17 @@ static void quantize_block(float *v, int had, int rnd, uint64_t seed, uint32_t s
         codes[i] = (uint8_t)((rnd == ORC_SR) ? orc_e2m1_encode_sr(t, orc_rand32(seed, idx0 + (uint64_t)i))
                                              : orc_e2m1_encode_rne(t));
     }
+}
+
+/* v[0..31]: the block, widened to fp32, in order along the contraction axis.
+ * idx0: linear index of element 0 of the block in the quantised output. */
+static void quantize_block(float *v, int had, int rnd, uint64_t seed, uint32_t sign_mask,
+                           uint64_t idx0, uint8_t *codes, uint8_t *scale_byte)
+{
+    rotate_block(v, had, sign_mask);
+    unsigned sb = orc_e8m0_from_amax_bits(amax_bits_of(v, MX_BLOCK));
+    *scale_byte = (uint8_t)sb;
+    encode_block(v, sb, rnd, seed, idx0, codes);
 }
 
 /* Quantise a row-major bf16 matrix x[rows][ld] (cols used per row).
@@ -260,6 +278,49 @@ int orc_quantize(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, int 
                            &s[r * (C / MX_BLOCK) + b]);
             for (int i = 0; i < MX_BLOCK; i += 2)
                 q[r * (C / 2) + (b * MX_BLOCK + i) / 2] = (uint8_t)(codes[i] | (codes[i + 1] << 4));
+        }
+    }
+    return 0;
+}
+
+/* 2D block quantisation (App. D, "32 x 32"): as orc_quantize, but one E8M0
+ * scale is shared by a whole 32 x 32 region = 32 consecutive output rows of
+ * one 32-element block column.  The scale follows the same rule as in 1D,
+ * applied to the largest magnitude of the region (after the rotation, which
+ * still runs along the contraction axis of each block); it is stored 32
+ * times, once per row, so the output has the 1D layout q[R][C/2], s[R][C/32]
+ * and feeds the same GEMM.  A NaN or an infinity anywhere in the region marks
+ * all 32 blocks (byte 0xFF, codes 0).  Returns 0, or 1 if R or C is not a
+ * multiple of 32. */
+int orc_quantize_2d(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, int axis, int had, int rnd,
+                    uint64_t seed, uint8_t *q, uint8_t *s)
+{
+    int64_t R = (axis == ORC_AXIS_LAST) ? rows : cols;
+    int64_t C = (axis == ORC_AXIS_LAST) ? cols : rows;
+    if (C % MX_BLOCK != 0 || R % MX_BLOCK != 0) return 1;
+    uint32_t sign_mask = orc_sign_mask(seed);
+#pragma omp parallel for schedule(static)
+    for (int64_t rt = 0; rt < R / MX_BLOCK; ++rt) {
+        for (int64_t b = 0; b < C / MX_BLOCK; ++b) {
+            float v[MX_BLOCK][MX_BLOCK];
+            uint8_t codes[MX_BLOCK];
+            for (int rr = 0; rr < MX_BLOCK; ++rr) {
+                int64_t r = rt * MX_BLOCK + rr;
+                for (int i = 0; i < MX_BLOCK; ++i) {
+                    int64_t c = b * MX_BLOCK + i;
+                    uint16_t h = (axis == ORC_AXIS_LAST) ? x[r * ld + c] : x[c * ld + r];
+                    v[rr][i] = orc_bf16_to_f32(h);
+                }
+                rotate_block(v[rr], had, sign_mask);
+            }
+            unsigned sb = orc_e8m0_from_amax_bits(amax_bits_of(&v[0][0], MX_BLOCK * MX_BLOCK));
+            for (int rr = 0; rr < MX_BLOCK; ++rr) {
+                int64_t r = rt * MX_BLOCK + rr;
+                s[r * (C / MX_BLOCK) + b] = (uint8_t)sb;
+                encode_block(v[rr], sb, rnd, seed, (uint64_t)(r * C + b * MX_BLOCK), codes);
+                for (int i = 0; i < MX_BLOCK; i += 2)
+                    q[r * (C / 2) + (b * MX_BLOCK + i) / 2] = (uint8_t)(codes[i] | (codes[i + 1] << 4));
+            }
         }
     }
     return 0;

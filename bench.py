@@ -230,6 +230,13 @@ def main() -> int:
         q_dual(rot[state["i"] % len(rot)], xq, xs, xtq, xts)
         state["i"] += 1
 
+    def dual_2d_rot():  # the 32 x 32 geometry, both outputs, no rotation
+        t = rot[state["i"] % len(rot)]
+        rc = L.mxfp4_quantize_2d(t.data_ptr(), M, K, K, mx.HAD_NONE, mx.RNE, 0, xq.data_ptr(), xs.data_ptr(),
+                                 xtq.data_ptr(), xts.data_ptr(), st)
+        assert rc == mx.OK
+        state["i"] += 1
+
     n_rot = 2 * len(rot)
     q_rot(q_rows)()
     q_rot(q_cols)()
@@ -237,10 +244,13 @@ def main() -> int:
     t_rows_cold = event_time_ms(q_rot(q_rows), n_rot, torch)
     t_cols_cold = event_time_ms(q_rot(q_cols), n_rot, torch)
     t_dual_cold = event_time_ms(dual_rot, n_rot, torch)
+    dual_2d_rot()
+    t_2d_cold = event_time_ms(dual_2d_rot, n_rot, torch)
     del rot
     gbs = lambda n_el, ms, bpe=BYTES_PER_ELEM: n_el * bpe / (ms * 1e-3) / 1e9
     quant_rows_gbs, quant_cols_gbs = gbs(M * K, t_rows_cold), gbs(M * K, t_cols_cold)
     quant_dual_gbs = gbs(M * K, t_dual_cold, BYTES_PER_ELEM_DUAL)
+    quant_2d_gbs = gbs(M * K, t_2d_cold, BYTES_PER_ELEM_DUAL)
 
     out = {
         "metric": "mxfp4_linear_gemm_tflops_incl_hadamard_quantize",
@@ -285,6 +295,8 @@ def main() -> int:
                                   "launch_ms": round(t_cols_cold, 4)},
             "dual_hbm_resident": {"achieved": round(quant_dual_gbs, 1), "frac": round(quant_dual_gbs / PEAK_HBM_GBS, 4),
                                   "launch_ms": round(t_dual_cold, 4), "bytes_per_element": BYTES_PER_ELEM_DUAL},
+            "dual_2d_hbm_resident": {"achieved": round(quant_2d_gbs, 1), "frac": round(quant_2d_gbs / PEAK_HBM_GBS, 4),
+                                     "launch_ms": round(t_2d_cold, 4), "bytes_per_element": BYTES_PER_ELEM_DUAL},
             "in_step_ms": {k: round(v, 4) for k, v in t_q.items()},
             "in_step_gbs_cache_warm": {k: round(gbs(elems[k], t_q[k]), 1) for k in elems},
         },

@@ -70,6 +70,12 @@ typedef enum {
 
 typedef enum { MXFP4_OUT_BF16 = 0, MXFP4_OUT_FP32 = 1 } mxfp4_out;
 
+/* Scale granularity (App. D). */
+typedef enum {
+    MXFP4_GEOM_1D = 0, /* one scale per 32 elements along the contraction axis (1x32 / 32x1)   */
+    MXFP4_GEOM_2D = 1  /* one scale per 32 x 32 region; needs M, N, K all multiples of 32      */
+} mxfp4_geometry;
+
 /* Recipe of one linear layer (one row of Table 1: stabiliser x rounding, all stages MXFP4). */
 typedef struct {
     int32_t hadamard;      /* mxfp4_hadamard, used for both operands of every GEMM             */
@@ -79,6 +85,8 @@ typedef struct {
     int32_t dx_dtype;      /* mxfp4_out for dX                                                  */
     int32_t dw_dtype;      /* mxfp4_out for dW                                                  */
     int32_t dw_accumulate; /* 1: dW += (fp32 only; gradient accumulation), 0: dW =             */
+    int32_t geometry;      /* mxfp4_geometry of every quantisation of the layer (App. D)        */
+    int32_t reserved;      /* must be 0                                                         */
 } mxfp4_linear_cfg;
 
 /*
@@ -114,6 +122,23 @@ int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
 int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
                         int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
                         void *hip_stream);
+
+/*
+ * 2D block quantisation (App. D, "32 x 32"): one E8M0 scale per 32 x 32 region instead of one per
+ * 32-element block.  The scale follows the same rule, applied to the largest magnitude of the
+ * region after the rotation (which still runs along each output's contraction axis); it is
+ * stored once per row of the region, so both outputs keep the layouts of mxfp4_quantize and feed
+ * mxfp4_gemm unchanged.  Without rotation the two outputs hold the same codes and scales,
+ * transposed: one quantisation of W serves Fprop and Dgrad.
+ *   x        bf16 [rows][ld], 16-byte aligned, ld % 8 == 0, rows % 32 == 0, cols % 32 == 0
+ *   q_last / s_last   row-wise output [rows][cols/2], [rows][cols/32], or both NULL
+ *   q_first / s_first column-wise output [cols][rows/2], [cols][rows/32], or both NULL
+ *   (at least one pair; q pointers 16-byte aligned).  A NaN or an infinity marks its whole
+ *   region (byte 0xFF, codes 0).  rows == 0 or cols == 0 is a valid empty call.
+ */
+int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                      int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
+                      void *hip_stream);
 
 /*
  * Block-scaled FP4 GEMM on quantised operands (the MXFP4 GEMM that replaces the FP8 GEMM of

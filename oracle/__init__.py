@@ -233,32 +233,39 @@ def f32_to_bf16_rne(x: np.ndarray) -> np.ndarray:
 # ---------------------------------------------------------------------------
 # the three training-stage GEMMs of one linear layer (App. C.1-C.3)
 # ---------------------------------------------------------------------------
-def linear_fwd_operands(x, w, had=HAD_NONE, rnd=RNE, seed=0):
+GEOM_1D, GEOM_2D = 0, 1
+
+
+def _q(geom):
+    return quantize_2d if geom == GEOM_2D else quantize
+
+
+def linear_fwd_operands(x, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
     """Fprop Y = X W^T: both operands rotated/quantised along K (App. C.1)."""
-    return quantize(x, AXIS_LAST, had, rnd, seed), quantize(w, AXIS_LAST, had, rnd, seed)
+    return _q(geom)(x, AXIS_LAST, had, rnd, seed), _q(geom)(w, AXIS_LAST, had, rnd, seed)
 
 
-def linear_fwd(x, w, had=HAD_NONE, rnd=RNE, seed=0):
-    (xq, xs), (wq, ws) = linear_fwd_operands(x, w, had, rnd, seed)
+def linear_fwd(x, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
+    (xq, xs), (wq, ws) = linear_fwd_operands(x, w, had, rnd, seed, geom)
     return gemm(xq, xs, wq, ws)
 
 
-def linear_dgrad_operands(dy, w, had=HAD_NONE, rnd=RNE, seed=0):
+def linear_dgrad_operands(dy, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
     """Dgrad dX = dY W: contraction over N; dY[M,N] along its last axis, W[N,K]
     along its first axis (giving W^T rows) (App. C.2)."""
-    return quantize(dy, AXIS_LAST, had, rnd, seed), quantize(w, AXIS_FIRST, had, rnd, seed)
+    return _q(geom)(dy, AXIS_LAST, had, rnd, seed), _q(geom)(w, AXIS_FIRST, had, rnd, seed)
 
 
-def linear_wgrad_operands(dy, x, had=HAD_NONE, rnd=RNE, seed=0):
+def linear_wgrad_operands(dy, x, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
     """Wgrad dW = dY^T X: contraction over tokens M; both operands quantised down
     their first axis (App. C.3)."""
-    return quantize(dy, AXIS_FIRST, had, rnd, seed), quantize(x, AXIS_FIRST, had, rnd, seed)
+    return _q(geom)(dy, AXIS_FIRST, had, rnd, seed), _q(geom)(x, AXIS_FIRST, had, rnd, seed)
 
 
-def linear_bwd(dy, x, w, had=HAD_NONE, rnd=RNE, seed=0):
+def linear_bwd(dy, x, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
     """Returns ((dX, absum_dX), (dW, absum_dW))."""
-    (gq, gs), (wtq, wts) = linear_dgrad_operands(dy, w, had, rnd, seed)
+    (gq, gs), (wtq, wts) = linear_dgrad_operands(dy, w, had, rnd, seed, geom)
     dx = gemm(gq, gs, wtq, wts)
-    (gtq, gts), (xtq, xts) = linear_wgrad_operands(dy, x, had, rnd, seed)
+    (gtq, gts), (xtq, xts) = linear_wgrad_operands(dy, x, had, rnd, seed, geom)
     dw = gemm(gtq, gts, xtq, xts)
     return dx, dw

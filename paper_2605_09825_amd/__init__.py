@@ -20,8 +20,9 @@ AXIS_LAST, AXIS_FIRST = 0, 1
 HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16 = 0, 1, 2, 3
 RNE, SR = 0, 1
 OUT_BF16, OUT_FP32 = 0, 1
+GEOM_1D, GEOM_2D = 0, 1
 
-EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_gemm", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
+EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_gemm", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
            "mxfp4_linear_fwd_save", "mxfp4_linear_bwd_saved", "mxfp4_linear_saved_bytes",
            "mxfp4_linear_saved_layout", "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout",
            "mxfp4_status_string")
@@ -31,7 +32,7 @@ class LinearCfg(ctypes.Structure):
     """mxfp4_linear_cfg"""
     _fields_ = [("hadamard", ctypes.c_int32), ("rounding", ctypes.c_int32), ("seed", ctypes.c_uint64),
                 ("y_dtype", ctypes.c_int32), ("dx_dtype", ctypes.c_int32), ("dw_dtype", ctypes.c_int32),
-                ("dw_accumulate", ctypes.c_int32)]
+                ("dw_accumulate", ctypes.c_int32), ("geometry", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class Mxfp4Error(RuntimeError):
@@ -56,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, u64, vp, vp, vp]
         L.mxfp4_quantize_dual.restype = ci
         L.mxfp4_quantize_dual.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp, vp, vp]
+        L.mxfp4_quantize_2d.restype = ci
+        L.mxfp4_quantize_2d.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp, vp, vp]
         L.mxfp4_linear_fwd_save.restype = ci
         L.mxfp4_linear_fwd_save.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp, sz, vp]
         L.mxfp4_linear_bwd_saved.restype = ci
@@ -138,6 +141,25 @@ def mxfp4_quantize_dual(x, hadamard: int = HAD_NONE, rounding: int = RNE, seed: 
     return ql, sl, qf, sf
 
 
+def mxfp4_quantize_2d(x, hadamard: int = HAD_NONE, rounding: int = RNE, seed: int = 0, want_last: bool = True,
+                      want_first: bool = True, stream=None):
+    """32 x 32 block scaling: returns (q_last, s_last, q_first, s_first); an output not wanted is None."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and (x.numel() == 0 or x.stride(1) == 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, x.stride(0))
+    u8 = dict(dtype=torch.uint8, device=x.device)
+    ql = sl = qf = sf = None
+    if want_last:
+        ql, sl = torch.empty((rows, cols // 2), **u8), torch.empty((rows, cols // 32), **u8)
+    if want_first:
+        qf, sf = torch.empty((cols, rows // 2), **u8), torch.empty((cols, rows // 32), **u8)
+    _check("mxfp4_quantize_2d", lib().mxfp4_quantize_2d(_ptr(x), rows, cols, ld, hadamard, rounding,
+                                                        seed & (2**64 - 1), _ptr(ql), _ptr(sl), _ptr(qf), _ptr(sf),
+                                                        _stream_ptr(stream)))
+    return ql, sl, qf, sf
+
+
 def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumulate: bool = False, stream=None):
     """out[i][j] (+)= sum_c A[i][c] B[j][c] on canonical quantised operands (uint8 CUDA tensors)."""
     import torch
@@ -165,8 +187,10 @@ def mxfp4_linear_workspace_layout(M: int, N: int, K: int, bwd: bool):
 
 
 def make_cfg(hadamard: int = HAD_NONE, rounding: int = RNE, seed: int = 0, y_dtype: int = OUT_BF16,
-             dx_dtype: int = OUT_BF16, dw_dtype: int = OUT_FP32, dw_accumulate: bool = False) -> LinearCfg:
-    return LinearCfg(hadamard, rounding, seed & (2**64 - 1), y_dtype, dx_dtype, dw_dtype, int(dw_accumulate))
+             dx_dtype: int = OUT_BF16, dw_dtype: int = OUT_FP32, dw_accumulate: bool = False,
+             geometry: int = GEOM_1D) -> LinearCfg:
+    return LinearCfg(hadamard, rounding, seed & (2**64 - 1), y_dtype, dx_dtype, dw_dtype, int(dw_accumulate),
+                     geometry, 0)
 
 
 def mxfp4_linear_fwd(x, w, cfg: LinearCfg, y=None, workspace=None, stream=None):

@@ -128,6 +128,8 @@ int check_cfg(const mxfp4_linear_cfg *cfg)
         if (dts[i] != MXFP4_OUT_BF16 && dts[i] != MXFP4_OUT_FP32) return MXFP4_EINVAL;
     if (cfg->dw_accumulate != 0 && cfg->dw_accumulate != 1) return MXFP4_EINVAL;
     if (cfg->dw_accumulate == 1 && cfg->dw_dtype != MXFP4_OUT_FP32) return MXFP4_EINVAL;
+    if (cfg->geometry != MXFP4_GEOM_1D && cfg->geometry != MXFP4_GEOM_2D) return MXFP4_EINVAL;
+    if (cfg->reserved != 0) return MXFP4_EINVAL;
     return MXFP4_OK;
 }
 
@@ -181,6 +183,36 @@ int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t 
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
+int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                      int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
+                      void *hip_stream)
+{
+    const bool want_last = q_last || s_last, want_first = q_first || s_first;
+    if (hadamard < MXFP4_HAD_NONE || hadamard > MXFP4_HAD_DET16) return MXFP4_EINVAL;
+    if (rounding != MXFP4_RNE && rounding != MXFP4_SR) return MXFP4_EINVAL;
+    if (rows < 0 || cols < 0) return MXFP4_ESHAPE;
+    if (rows == 0 || cols == 0) return MXFP4_OK;
+    if (!want_last && !want_first) return MXFP4_EINVAL;
+    if ((rows % 32) != 0 || (cols % 32) != 0) return MXFP4_ESHAPE;
+    // per requested output, the single-axis argument rules
+    if (want_last) {
+        int rc = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_LAST, hadamard, rounding, q_last, s_last);
+        if (rc >= 0) return rc;
+    }
+    if (want_first) {
+        int rc = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_FIRST, hadamard, rounding, q_first, s_first);
+        if (rc >= 0) return rc;
+    }
+    if (!aligned(x_bf16, 16) || (ld_elems % 8) != 0) return MXFP4_EALIGN;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    QuantArgs a{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
+                static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
+    a.q_row = static_cast<uint8_t *>(q_last);
+    a.s_row = static_cast<uint8_t *>(s_last);
+    hipError_t e = launch_quantize_2d(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
 int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_s, int64_t R_a, int64_t R_b,
                int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream)
 {
@@ -192,6 +224,24 @@ int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_
                R_a, R_b, C, out, ld_out, out_dtype == MXFP4_OUT_FP32, accumulate};
     hipError_t e = launch_gemm(g, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
+// One dense tensor of a linear layer, quantised in the layer's geometry: the row-wise output (q_last, s_last),
+// the column-wise one (q_first, s_first), or both from one pass (a null pair = not wanted).
+static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t rows, int64_t cols, uint8_t *q_last,
+                            uint8_t *s_last, uint8_t *q_first, uint8_t *s_first, void *hip_stream)
+{
+    if (cfg->geometry == MXFP4_GEOM_2D)
+        return mxfp4_quantize_2d(x, rows, cols, cols, cfg->hadamard, cfg->rounding, cfg->seed, q_last, s_last,
+                                 q_first, s_first, hip_stream);
+    if (q_last && q_first)
+        return mxfp4_quantize_dual(x, rows, cols, cols, cfg->hadamard, cfg->rounding, cfg->seed, q_last, s_last,
+                                   q_first, s_first, hip_stream);
+    if (q_last)
+        return mxfp4_quantize(x, rows, cols, cols, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, q_last,
+                              s_last, hip_stream);
+    return mxfp4_quantize(x, rows, cols, cols, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, q_first,
+                          s_first, hip_stream);
 }
 
 size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd)
@@ -222,16 +272,15 @@ int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N
     int rc = check_cfg(cfg);
     if (rc != MXFP4_OK) return rc;
     if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0) return MXFP4_ESHAPE;
+    if (cfg->geometry == MXFP4_GEOM_2D && ((M % 32) != 0 || (N % 32) != 0)) return MXFP4_ESHAPE;
     if (!x || !w || !y || !workspace) return MXFP4_EINVAL;
     const FwdLayout L = fwd_layout(M, N, K);
     if (workspace_bytes < L.total) return MXFP4_EWORKSPACE;
     if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    rc = mxfp4_quantize(x, M, K, K, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.xq, ws + L.xs,
-                        hip_stream);
+    rc = quantize_operand(cfg, x, M, K, ws + L.xq, ws + L.xs, nullptr, nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    rc = mxfp4_quantize(w, N, K, K, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.wq, ws + L.ws,
-                        hip_stream);
+    rc = quantize_operand(cfg, w, N, K, ws + L.wq, ws + L.ws, nullptr, nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
     return mxfp4_gemm(ws + L.xq, ws + L.xs, ws + L.wq, ws + L.ws, M, N, K, y, N, cfg->y_dtype, 0, hip_stream);
 }
@@ -245,6 +294,7 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
     if (M <= 0 || N <= 0 || K <= 0) return MXFP4_ESHAPE;
     if (dx && ((N % 32) != 0 || (K % 2) != 0)) return MXFP4_ESHAPE;
     if (dw && ((M % 32) != 0 || (N % 2) != 0 || (K % 2) != 0)) return MXFP4_ESHAPE;
+    if (cfg->geometry == MXFP4_GEOM_2D && ((M % 32) != 0 || (N % 32) != 0 || (K % 32) != 0)) return MXFP4_ESHAPE;
     if (!dx && !dw) return MXFP4_OK;
     if (!dy || !workspace) return MXFP4_EINVAL;
     if ((dx && !w) || (dw && !x)) return MXFP4_EINVAL;
@@ -255,32 +305,18 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
         return MXFP4_EALIGN;
     if ((N % 8) != 0 || (K % 8) != 0) return MXFP4_EALIGN;  // dense bf16 rows must stay 16-byte aligned
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    const bool dual = dx && dw && (N % 32) == 0;  // dY is needed both ways: read it once
-    if (dual) {
-        rc = mxfp4_quantize_dual(dy, M, N, N, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq, ws + L.gs,
-                                 ws + L.gtq, ws + L.gts, hip_stream);
-        if (rc != MXFP4_OK) return rc;
-    }
+    // dY is needed row-wise for Dgrad and column-wise for Wgrad: one pass when both are asked
+    rc = quantize_operand(cfg, dy, M, N, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
+                          dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
+    if (rc != MXFP4_OK) return rc;
     if (dx) {
-        if (!dual) {
-            rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq,
-                                ws + L.gs, hip_stream);
-            if (rc != MXFP4_OK) return rc;
-        }
-        rc = mxfp4_quantize(w, N, K, K, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.wtq,
-                            ws + L.wts, hip_stream);
+        rc = quantize_operand(cfg, w, N, K, nullptr, nullptr, ws + L.wtq, ws + L.wts, hip_stream);
         if (rc != MXFP4_OK) return rc;
         rc = mxfp4_gemm(ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
         if (rc != MXFP4_OK) return rc;
     }
     if (dw) {
-        if (!dual) {
-            rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gtq,
-                                ws + L.gts, hip_stream);
-            if (rc != MXFP4_OK) return rc;
-        }
-        rc = mxfp4_quantize(x, M, K, K, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.xtq,
-                            ws + L.xts, hip_stream);
+        rc = quantize_operand(cfg, x, M, K, nullptr, nullptr, ws + L.xtq, ws + L.xts, hip_stream);
         if (rc != MXFP4_OK) return rc;
         rc = mxfp4_gemm(ws + L.gtq, ws + L.gts, ws + L.xtq, ws + L.xts, N, K, M, dw, K, cfg->dw_dtype,
                         cfg->dw_accumulate, hip_stream);
@@ -319,11 +355,9 @@ int mxfp4_linear_fwd_save(const void *x, const void *w, void *y, int64_t M, int6
         return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     uint8_t *sv = static_cast<uint8_t *>(saved);
-    rc = mxfp4_quantize_dual(x, M, K, K, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.xq, ws + L.xs, sv + S.xtq,
-                             sv + S.xts, hip_stream);
+    rc = quantize_operand(cfg, x, M, K, ws + L.xq, ws + L.xs, sv + S.xtq, sv + S.xts, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    rc = mxfp4_quantize_dual(w, N, K, K, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.wq, ws + L.ws, sv + S.wtq,
-                             sv + S.wts, hip_stream);
+    rc = quantize_operand(cfg, w, N, K, ws + L.wq, ws + L.ws, sv + S.wtq, sv + S.wts, hip_stream);
     if (rc != MXFP4_OK) return rc;
     return mxfp4_gemm(ws + L.xq, ws + L.xs, ws + L.wq, ws + L.ws, M, N, K, y, N, cfg->y_dtype, 0, hip_stream);
 }
@@ -345,15 +379,8 @@ int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes
         return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const uint8_t *sv = static_cast<const uint8_t *>(saved);
-    if (dx && dw)
-        rc = mxfp4_quantize_dual(dy, M, N, N, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq, ws + L.gs,
-                                 ws + L.gtq, ws + L.gts, hip_stream);
-    else if (dx)
-        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gq,
-                            ws + L.gs, hip_stream);
-    else
-        rc = mxfp4_quantize(dy, M, N, N, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, ws + L.gtq,
-                            ws + L.gts, hip_stream);
+    rc = quantize_operand(cfg, dy, M, N, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
+                          dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
     if (dx) {
         rc = mxfp4_gemm(ws + L.gq, ws + L.gs, sv + S.wtq, sv + S.wts, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);

@@ -17,6 +17,8 @@
 //   * both at once: the column-wise workgroup tile, whose 256 x 128 elements are also
 //     parked in LDS and read back as row-wise blocks; memory delivers the tensor once
 //     for the two outputs.
+//   * 32 x 32 geometry (App. D): the same kernel with the block maxima reduced over the
+//     16 lanes that share a region before the codes are formed.
 #include "mxfp4_internal.h"
 
 namespace mxfp4 {
@@ -86,11 +88,9 @@ __device__ __forceinline__ uint32_t sr_code(float t, uint32_t r)
     return code | ((__float_as_uint(t) >> 28) & 8u);
 }
 
-// v: the block widened to fp32, in contraction order.  idx0: linear index of element 0
-// in the quantised output (stochastic rounding counter).
-template <int HAD, int RND>
-__device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask, RngKey key, uint64_t idx0,
-                                             uint4 &codes, uint32_t &scale_byte)
+// Optional sign flips and rotation of one block, in place (App. A.2).
+template <int HAD>
+__device__ __forceinline__ void rotate_block(float (&v)[32], uint32_t sign_mask)
 {
     if (HAD == HAD_RANDSIGN) {
 #pragma unroll
@@ -107,10 +107,13 @@ __device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask,
 #pragma unroll
         for (int i = 0; i < 32; ++i) v[i] = v[i] * 0.25f;
     }
+}
 
-    // block maximum on the bit patterns (NaN and infinity compare above every finite value), without
-    // clearing 32 sign bits: the unsigned maximum is the largest-magnitude negative value if there is
-    // one, the signed maximum (from 0) the largest positive one
+// Block maximum on the bit patterns (NaN and infinity compare above every finite value), without
+// clearing 32 sign bits: the unsigned maximum is the largest-magnitude negative value if there is
+// one, the signed maximum (from 0) the largest positive one.
+__device__ __forceinline__ uint32_t amax_bits(const float (&v)[32])
+{
     uint32_t mu = 0;
     int32_t mi = 0;
 #pragma unroll
@@ -120,7 +123,16 @@ __device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask,
         mi = (int32_t)b > mi ? (int32_t)b : mi;
     }
     mu &= 0x7FFFFFFFu;
-    const uint32_t amax = (uint32_t)mi > mu ? (uint32_t)mi : mu;
+    return (uint32_t)mi > mu ? (uint32_t)mi : mu;
+}
+
+// FP4 codes of one rotated block under the scale that follows from the shared maximum `amax` (bit
+// pattern): eq. (1) with the OCP scale rule.  idx0: linear index of element 0 in the quantised output
+// (stochastic rounding counter).
+template <int RND>
+__device__ __forceinline__ void encode_scaled(const float (&v)[32], uint32_t amax, RngKey key, uint64_t idx0,
+                                              uint4 &codes, uint32_t &scale_byte)
+{
     uint32_t eb = amax >> 23;
     bool bad = (eb == 255u);
     uint32_t sb = eb > 2u ? eb - 2u : 0u;  // eb <= 254 here, so sb <= 252
@@ -155,6 +167,15 @@ __device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask,
         }
     }
     codes = bad ? make_uint4(0, 0, 0, 0) : make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// v: the block widened to fp32, in contraction order; 1D scaling (one scale per block).
+template <int HAD, int RND>
+__device__ __forceinline__ void encode_block(float (&v)[32], uint32_t sign_mask, RngKey key, uint64_t idx0,
+                                             uint4 &codes, uint32_t &scale_byte)
+{
+    rotate_block<HAD>(v, sign_mask);
+    encode_scaled<RND>(v, amax_bits(v), key, idx0, codes, scale_byte);
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -210,16 +231,27 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
 // Workgroup tile: 256 rows (8 row blocks, one per wave) x 128 columns (2 per lane).
 constexpr int CT_COLS = 128, CT_RB = 8;
 
-// DUAL: additionally emit the row-wise quantisation q_row[rows][cols/2], s_row[rows][cols/32] of the same
-// tile (needs cols % 32 == 0).  Each wave parks its 32 x 128 elements in LDS and reads them back as 128
-// row blocks, two per lane, four lanes per row, so the tensor is fetched from memory once.  The parked
+// MODE_DUAL: additionally emit the row-wise quantisation q_row[rows][cols/2], s_row[rows][cols/32] of the
+// same tile (needs cols % 32 == 0).  Each wave parks its 32 x 128 elements in LDS and reads them back as
+// 128 row blocks, two per lane, four lanes per row, so the tensor is fetched from memory once.  The parked
 // tile and the regrouping buffers of the column-wise output share the same LDS.
+// MODE_2D: the 32 x 32 geometry of App. D: one scale per 32 x 32 region (a wave's tile holds four), taken
+// from the largest magnitude of the region after the rotation; either output may be switched off (null
+// q/s or q_row/s_row).  Each phase runs twice over its data: first the maxima, reduced across the 16 lanes
+// that share a region, then the codes.
+constexpr int MODE_COLS = 0, MODE_DUAL = 1, MODE_2D = 2;
 constexpr int RAW_PITCH = 272;  // bytes per parked row: 256 + 16, so that the 16-byte reads below (16 lanes =
                                 // 4 rows x 4 blocks per issue) and the dword writes touch every bank once
 constexpr int LDS_Q_BYTES = CT_RB * (CT_COLS + 1) * 16, LDS_S_BYTES = CT_COLS * CT_RB;
 constexpr int LDS_RAW_BYTES = CT_RB * 32 * RAW_PITCH;
 
-template <int HAD, int RND, bool DUAL>
+__device__ __forceinline__ uint32_t max_across(uint32_t m, int xor_mask)
+{
+    const uint32_t o = (uint32_t)__shfl_xor((int)m, xor_mask);
+    return o > m ? o : m;
+}
+
+template <int HAD, int RND, int MODE>
 __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t rows,
                                                             int64_t cols, int64_t ld, uint32_t sign_mask,
                                                             RngKey key, uint8_t *__restrict__ q,
@@ -227,7 +259,8 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
                                                             uint32_t col_groups, uint8_t *__restrict__ q_row,
                                                             uint8_t *__restrict__ s_row, int s_row_vec4)
 {
-    constexpr int LDS_BYTES = (DUAL && LDS_RAW_BYTES > LDS_Q_BYTES + LDS_S_BYTES) ? LDS_RAW_BYTES
+    constexpr bool PARK = (MODE != MODE_COLS);
+    constexpr int LDS_BYTES = (PARK && LDS_RAW_BYTES > LDS_Q_BYTES + LDS_S_BYTES) ? LDS_RAW_BYTES
                                                                                   : LDS_Q_BYTES + LDS_S_BYTES;
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
     uint4(*lds_q)[CT_COLS + 1] = reinterpret_cast<uint4(*)[CT_COLS + 1]>(lds);
@@ -241,6 +274,8 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
     const int64_t rb = rb0 + w;
     const int64_t col = c0 + 2 * lane;
     const bool active = (rb < nrb) && (col < cols);
+    const bool want_row = (MODE == MODE_DUAL) || (MODE == MODE_2D && q_row != nullptr);
+    const bool want_col = (MODE != MODE_2D) || (q != nullptr);
 
     uint32_t raw[32];
     if (active) {
@@ -252,7 +287,7 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
         for (int i = 0; i < 32; ++i) raw[i] = 0;
     }
 
-    if (DUAL) {
+    if (PARK && want_row) {
         uint8_t *mine = lds + w * (32 * RAW_PITCH);
 #pragma unroll
         for (int i = 0; i < 32; ++i) *reinterpret_cast<uint32_t *>(mine + i * RAW_PITCH + 4 * lane) = raw[i];
@@ -261,6 +296,27 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
         const int64_t colb = c0 + 32 * cb;
         const int64_t bpr = cols >> 5;
         const bool on = (rb < nrb) && (colb < cols);
+        uint32_t region_max = 0;
+        if (MODE == MODE_2D) {
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int r = (lane >> 2) + 16 * pass;
+                const uint4 *p = reinterpret_cast<const uint4 *>(mine + r * RAW_PITCH + 64 * cb);
+                uint4 rraw[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) rraw[j] = p[j];
+                float v[32];
+                widen(rraw, v);
+                rotate_block<HAD>(v, sign_mask);
+                const uint32_t m = amax_bits(v);
+                region_max = m > region_max ? m : region_max;
+            }
+            // the 32 rows of one region: the 16 lanes with this lane's (lane & 3), two rows each
+            region_max = max_across(region_max, 4);
+            region_max = max_across(region_max, 8);
+            region_max = max_across(region_max, 16);
+            region_max = max_across(region_max, 32);
+        }
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             const int r = (lane >> 2) + 16 * pass;
@@ -271,9 +327,11 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
             for (int j = 0; j < 4; ++j) rraw[j] = p[j];
             float v[32];
             widen(rraw, v);
+            rotate_block<HAD>(v, sign_mask);
             uint4 codes;
             uint32_t sb;
-            encode_block<HAD, RND>(v, sign_mask, key, (uint64_t)row * (uint64_t)cols + (uint64_t)colb, codes, sb);
+            encode_scaled<RND>(v, MODE == MODE_2D ? region_max : amax_bits(v), key,
+                               (uint64_t)row * (uint64_t)cols + (uint64_t)colb, codes, sb);
             const int64_t g = row * bpr + (colb >> 5);
             if (on) reinterpret_cast<uint4 *>(q_row)[g] = codes;
             // the four scale bytes of one row of the tile go out as one dword where they can
@@ -289,16 +347,35 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
         }
         __syncthreads();  // every wave is done with the parked tile: its LDS becomes the regrouping buffers
     }
+    if (!want_col) return;  // (uniform over the grid)
 
+    uint32_t region_max = 0;
+    if (MODE == MODE_2D) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            float v[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) v[i] = j == 0 ? bf16_lo(raw[i]) : bf16_hi(raw[i]);
+            rotate_block<HAD>(v, sign_mask);
+            const uint32_t m = amax_bits(v);
+            region_max = m > region_max ? m : region_max;
+        }
+        // the 32 columns of one region: 16 consecutive lanes, two columns each
+        region_max = max_across(region_max, 1);
+        region_max = max_across(region_max, 2);
+        region_max = max_across(region_max, 4);
+        region_max = max_across(region_max, 8);
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         float v[32];
 #pragma unroll
         for (int i = 0; i < 32; ++i) v[i] = j == 0 ? bf16_lo(raw[i]) : bf16_hi(raw[i]);
+        rotate_block<HAD>(v, sign_mask);
         uint4 codes;
         uint32_t sb;
-        encode_block<HAD, RND>(v, sign_mask, key, (uint64_t)(col + j) * (uint64_t)rows + (uint64_t)rb * 32u,
-                               codes, sb);
+        encode_scaled<RND>(v, MODE == MODE_2D ? region_max : amax_bits(v), key,
+                           (uint64_t)(col + j) * (uint64_t)rows + (uint64_t)rb * 32u, codes, sb);
         lds_q[w][2 * lane + j] = codes;
         lds_s[2 * lane + j][w] = (uint8_t)sb;
     }
@@ -341,7 +418,7 @@ hipError_t launch_rows_h(const QuantArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int HAD, bool DUAL>
+template <int HAD, int MODE>
 hipError_t launch_cols_h(const QuantArgs &a, hipStream_t st)
 {
     const int64_t nrb = a.rows / 32;
@@ -351,12 +428,13 @@ hipError_t launch_cols_h(const QuantArgs &a, hipStream_t st)
     const RngKey key = make_key(a.seed);
     const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
     const int s_vec8 = ((nrb % 8) == 0) && ((reinterpret_cast<uintptr_t>(a.s) % 8) == 0);
-    const int s_row_vec4 = DUAL && (((a.cols / 32) % 4) == 0) && ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
+    const int s_row_vec4 = MODE != MODE_COLS && a.s_row != nullptr && (((a.cols / 32) % 4) == 0) &&
+                           ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
     if (a.rounding == RND_RNE)
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, DUAL>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, MODE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
                            a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4);
     else
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, DUAL>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, MODE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
                            a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4);
     return hipGetLastError();
 }
@@ -376,20 +454,30 @@ hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st)
 hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st)
 {
     switch (a.hadamard) {
-        case HAD_NONE: return launch_cols_h<HAD_NONE, false>(a, st);
-        case HAD_DET: return launch_cols_h<HAD_DET, false>(a, st);
-        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, false>(a, st);
-        default: return launch_cols_h<HAD_DET16, false>(a, st);
+        case HAD_NONE: return launch_cols_h<HAD_NONE, MODE_COLS>(a, st);
+        case HAD_DET: return launch_cols_h<HAD_DET, MODE_COLS>(a, st);
+        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE_COLS>(a, st);
+        default: return launch_cols_h<HAD_DET16, MODE_COLS>(a, st);
     }
 }
 
 hipError_t launch_quantize_dual(const QuantArgs &a, hipStream_t st)
 {
     switch (a.hadamard) {
-        case HAD_NONE: return launch_cols_h<HAD_NONE, true>(a, st);
-        case HAD_DET: return launch_cols_h<HAD_DET, true>(a, st);
-        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, true>(a, st);
-        default: return launch_cols_h<HAD_DET16, true>(a, st);
+        case HAD_NONE: return launch_cols_h<HAD_NONE, MODE_DUAL>(a, st);
+        case HAD_DET: return launch_cols_h<HAD_DET, MODE_DUAL>(a, st);
+        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE_DUAL>(a, st);
+        default: return launch_cols_h<HAD_DET16, MODE_DUAL>(a, st);
+    }
+}
+
+hipError_t launch_quantize_2d(const QuantArgs &a, hipStream_t st)
+{
+    switch (a.hadamard) {
+        case HAD_NONE: return launch_cols_h<HAD_NONE, MODE_2D>(a, st);
+        case HAD_DET: return launch_cols_h<HAD_DET, MODE_2D>(a, st);
+        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE_2D>(a, st);
+        default: return launch_cols_h<HAD_DET16, MODE_2D>(a, st);
     }
 }
 

@@ -143,6 +143,26 @@ def test_dual_and_saved_argument_errors(L):
     assert b(P, S, need_s, None, None, M, N, K, c, W, need_b, None) == mx.OK  # nothing asked
 
 
+def test_2d_geometry_argument_errors(L):
+    d = L.mxfp4_quantize_2d
+    assert d(P, 64, 64, 64, 9, 0, 0, P, P, P, P, None) == mx.EINVAL        # hadamard
+    assert d(P, 64, 64, 64, 0, 0, 0, None, None, None, None, None) == mx.EINVAL  # no output asked
+    assert d(P, 64, 64, 64, 0, 0, 0, P, None, None, None, None) == mx.EINVAL     # half a pair
+    assert d(P, 48, 64, 64, 0, 0, 0, P, P, None, None, None) == mx.ESHAPE  # rows % 32 even for the row-wise output
+    assert d(P, 64, 48, 48, 0, 0, 0, None, None, P, P, None) == mx.ESHAPE
+    assert d(P, 64, 64, 68, 0, 0, 0, P, P, None, None, None) == mx.EALIGN
+    assert d(P + 4, 64, 64, 64, 0, 0, 0, None, None, P, P, None) == mx.EALIGN
+    assert d(None, 0, 64, 64, 0, 0, 0, None, None, None, None, None) == mx.OK
+    bad = mx.make_cfg(geometry=7)
+    W = 0x100000
+    need = mx.mxfp4_linear_workspace_bytes(64, 96, 128, bad, False)
+    assert L.mxfp4_linear_fwd(P, P, P, 64, 96, 128, ctypes.byref(bad), W, need, None) == mx.EINVAL
+    g2 = mx.make_cfg(geometry=mx.GEOM_2D)
+    assert L.mxfp4_linear_fwd(P, P, P, 48, 96, 128, ctypes.byref(g2), W, need, None) == mx.ESHAPE
+    needb = mx.mxfp4_linear_workspace_bytes(64, 96, 128, g2, True)
+    assert L.mxfp4_linear_bwd(P, P, P, P, None, 64, 96, 136, ctypes.byref(g2), W, needb, None) == mx.ESHAPE
+
+
 def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
     monkeypatch.setattr(mx, "_lib", None)
     monkeypatch.setattr(mx, "LIB_PATH", str(tmp_path / "nope.so"))

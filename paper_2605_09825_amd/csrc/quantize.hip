@@ -257,7 +257,8 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
                                                             RngKey key, uint8_t *__restrict__ q,
                                                             uint8_t *__restrict__ s, int s_vec8,
                                                             uint32_t col_groups, uint8_t *__restrict__ q_row,
-                                                            uint8_t *__restrict__ s_row, int s_row_vec4)
+                                                            uint8_t *__restrict__ s_row, int s_row_vec4,
+                                                            uint32_t band_rows)
 {
     constexpr bool PARK = (MODE != MODE_COLS);
     constexpr int LDS_BYTES = (PARK && LDS_RAW_BYTES > LDS_Q_BYTES + LDS_S_BYTES) ? LDS_RAW_BYTES
@@ -267,7 +268,27 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
     uint8_t(*lds_s)[CT_RB] = reinterpret_cast<uint8_t(*)[CT_RB]>(lds + LDS_Q_BYTES);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const uint32_t by = blockIdx.x / col_groups, bx = blockIdx.x - by * col_groups;
+    // Tile order.  A tile contributes only 8 scale bytes per column (4 per row in the row-wise output), far less
+    // than the 64 bytes the memory side writes at once, and the 8 XCDs (workgroup id mod 8) have separate L2s
+    // that cannot merge each other's partial writes.  With band_rows > 0 each XCD takes a contiguous run of the
+    // tile sequence, and the sequence walks the grid in bands of band_rows tile rows, tile rows fastest, so that
+    // the tiles completing a 64-byte piece of either scale stream meet in one L2 (measured: write requests fall
+    // from 1.18x to 1.00x the algorithmic count; worth 8 % on a 16384 x 14336 tensor, nothing on tensors
+    // so small that a CU sees only a few tiles, which keep the plain order band_rows = 0).
+    uint32_t by, bx;
+    if (band_rows == 0) {
+        by = blockIdx.x / col_groups;
+        bx = blockIdx.x - by * col_groups;
+    } else {
+        const uint32_t nb = gridDim.x, xcd = blockIdx.x & 7, per = nb >> 3, rem = nb & 7;
+        const uint32_t start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+        const uint32_t lb = start + (blockIdx.x >> 3);
+        const uint32_t row_groups = nb / col_groups, span = band_rows * col_groups;
+        const uint32_t band = lb / span, in = lb - band * span;
+        const uint32_t left = row_groups - band * band_rows, gm = left < band_rows ? left : band_rows;
+        bx = in / gm;
+        by = band * band_rows + (in - bx * gm);
+    }
     const int64_t c0 = (int64_t)bx * CT_COLS;
     const int64_t rb0 = (int64_t)by * CT_RB;
     const int64_t nrb = rows >> 5;
@@ -428,14 +449,15 @@ hipError_t launch_cols_h(const QuantArgs &a, hipStream_t st)
     const RngKey key = make_key(a.seed);
     const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
     const int s_vec8 = ((nrb % 8) == 0) && ((reinterpret_cast<uintptr_t>(a.s) % 8) == 0);
+    const uint32_t band_rows = grid.x < 2048 ? 0u : (MODE == MODE_COLS ? 16u : 2u);
     const int s_row_vec4 = MODE != MODE_COLS && a.s_row != nullptr && (((a.cols / 32) % 4) == 0) &&
                            ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
     if (a.rounding == RND_RNE)
         hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, MODE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
-                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4);
+                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4, band_rows);
     else
         hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, MODE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
-                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4);
+                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4, band_rows);
     return hipGetLastError();
 }
 

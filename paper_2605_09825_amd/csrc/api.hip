@@ -164,9 +164,10 @@ int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
-int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
-                        int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
-                        void *hip_stream)
+// Argument checks of the two-output calls.  Return -1 and fill `a` when a launch is due, else the status to
+// hand back (MXFP4_OK for an empty tensor).
+static int prep_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard, int rounding,
+                     uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first, QuantArgs &a)
 {
     // the union of the two single-axis argument rules
     int rc = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_LAST, hadamard, rounding, q_last, s_last);
@@ -174,18 +175,15 @@ int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t 
     if (rc > 0) return rc;
     if (rc2 > 0) return rc2;
     if (rc == 0 || rc2 == 0) return MXFP4_OK;
-    if (!device_ok()) return MXFP4_EDEVICE;
-    QuantArgs a{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
-                static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
+    a = QuantArgs{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
+                  static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
     a.q_row = static_cast<uint8_t *>(q_last);
     a.s_row = static_cast<uint8_t *>(s_last);
-    hipError_t e = launch_quantize_dual(a, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+    return -1;
 }
 
-int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
-                      int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
-                      void *hip_stream)
+static int prep_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard, int rounding,
+                   uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first, QuantArgs &a)
 {
     const bool want_last = q_last || s_last, want_first = q_first || s_first;
     if (hadamard < MXFP4_HAD_NONE || hadamard > MXFP4_HAD_DET16) return MXFP4_EINVAL;
@@ -204,12 +202,34 @@ int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld
         if (rc >= 0) return rc;
     }
     if (!aligned(x_bf16, 16) || (ld_elems % 8) != 0) return MXFP4_EALIGN;
-    if (!device_ok()) return MXFP4_EDEVICE;
-    QuantArgs a{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
-                static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
+    a = QuantArgs{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
+                  static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
     a.q_row = static_cast<uint8_t *>(q_last);
     a.s_row = static_cast<uint8_t *>(s_last);
-    hipError_t e = launch_quantize_2d(a, static_cast<hipStream_t>(hip_stream));
+    return -1;
+}
+
+int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                        int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
+                        void *hip_stream)
+{
+    QuantArgs a;
+    int rc = prep_dual(x_bf16, rows, cols, ld_elems, hadamard, rounding, seed, q_last, s_last, q_first, s_first, a);
+    if (rc >= 0) return rc;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    hipError_t e = launch_quantize_dual(a, nullptr, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
+int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                      int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
+                      void *hip_stream)
+{
+    QuantArgs a;
+    int rc = prep_2d(x_bf16, rows, cols, ld_elems, hadamard, rounding, seed, q_last, s_last, q_first, s_first, a);
+    if (rc >= 0) return rc;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    hipError_t e = launch_quantize_2d(a, nullptr, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
@@ -242,6 +262,36 @@ static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t 
                               s_last, hip_stream);
     return mxfp4_quantize(x, rows, cols, cols, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, q_first,
                           s_first, hip_stream);
+}
+
+// Both outputs of two dense tensors (the operands X and W of a forward call that also saves for the backward
+// call) in one launch.
+static int quantize_operand_pair(const mxfp4_linear_cfg *cfg, const void *x0, int64_t rows0, int64_t cols0,
+                                 uint8_t *ql0, uint8_t *sl0, uint8_t *qf0, uint8_t *sf0, const void *x1,
+                                 int64_t rows1, int64_t cols1, uint8_t *ql1, uint8_t *sl1, uint8_t *qf1,
+                                 uint8_t *sf1, void *hip_stream)
+{
+    const bool g2 = cfg->geometry == MXFP4_GEOM_2D;
+    QuantArgs a, b;
+    auto prep = g2 ? prep_2d : prep_dual;
+    int rc = prep(x0, rows0, cols0, cols0, cfg->hadamard, cfg->rounding, cfg->seed, ql0, sl0, qf0, sf0, a);
+    if (rc > 0) return rc;
+    int rc1 = prep(x1, rows1, cols1, cols1, cfg->hadamard, cfg->rounding, cfg->seed, ql1, sl1, qf1, sf1, b);
+    if (rc1 > 0) return rc1;
+    if (rc == 0 && rc1 == 0) return MXFP4_OK;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    auto tiles = [](const QuantArgs &t) { return ((t.cols + 127) / 128) * ((t.rows / 32 + 7) / 8); };
+    if (rc == 0 || rc1 == 0) {  // one of them is empty
+        e = g2 ? launch_quantize_2d(rc == 0 ? b : a, nullptr, st) : launch_quantize_dual(rc == 0 ? b : a, nullptr, st);
+    } else if (tiles(a) + tiles(b) >= (int64_t(1) << 31)) {  // too many workgroups for one grid
+        e = g2 ? launch_quantize_2d(a, nullptr, st) : launch_quantize_dual(a, nullptr, st);
+        if (e == hipSuccess) e = g2 ? launch_quantize_2d(b, nullptr, st) : launch_quantize_dual(b, nullptr, st);
+    } else {
+        e = g2 ? launch_quantize_2d(a, &b, st) : launch_quantize_dual(a, &b, st);
+    }
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
 size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd)
@@ -355,9 +405,8 @@ int mxfp4_linear_fwd_save(const void *x, const void *w, void *y, int64_t M, int6
         return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     uint8_t *sv = static_cast<uint8_t *>(saved);
-    rc = quantize_operand(cfg, x, M, K, ws + L.xq, ws + L.xs, sv + S.xtq, sv + S.xts, hip_stream);
-    if (rc != MXFP4_OK) return rc;
-    rc = quantize_operand(cfg, w, N, K, ws + L.wq, ws + L.ws, sv + S.wtq, sv + S.wts, hip_stream);
+    rc = quantize_operand_pair(cfg, x, M, K, ws + L.xq, ws + L.xs, sv + S.xtq, sv + S.xts, w, N, K, ws + L.wq,
+                               ws + L.ws, sv + S.wtq, sv + S.wts, hip_stream);
     if (rc != MXFP4_OK) return rc;
     return mxfp4_gemm(ws + L.xq, ws + L.xs, ws + L.wq, ws + L.ws, M, N, K, y, N, cfg->y_dtype, 0, hip_stream);
 }

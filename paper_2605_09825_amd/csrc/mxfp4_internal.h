@@ -21,10 +21,12 @@ hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st);
 // blocks down columns (32x1): q[cols][rows/2], s[cols][rows/32]
 hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st);
 // both from one pass over x: q, s as launch_quantize_cols; q_row, s_row as launch_quantize_rows
-hipError_t launch_quantize_dual(const QuantArgs &a, hipStream_t st);
+// (b, if not null: a second tensor in the same launch, same hadamard, rounding and seed; the two grids together
+// must stay below 2^31 workgroups)
+hipError_t launch_quantize_dual(const QuantArgs &a, const QuantArgs *b, hipStream_t st);
 // one scale per 32 x 32 region; the pair q, s (column-wise layout) or the pair q_row, s_row (row-wise layout)
 // may be null
-hipError_t launch_quantize_2d(const QuantArgs &a, hipStream_t st);
+hipError_t launch_quantize_2d(const QuantArgs &a, const QuantArgs *b, hipStream_t st);
 
 struct GemmArgs {
     const uint8_t *aq, *as, *bq, *bs;

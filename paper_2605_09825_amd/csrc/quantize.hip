@@ -251,15 +251,34 @@ __device__ __forceinline__ uint32_t max_across(uint32_t m, int xor_mask)
     return o > m ? o : m;
 }
 
+// One tensor's share of a launch.  A launch may carry two tensors (the two operands of a GEMM): workgroups
+// 0 .. nblocks-1 of the first job, then those of the second.
+struct TileJob {
+    const uint16_t *x;
+    int64_t rows, cols, ld;
+    uint8_t *q, *s, *q_row, *s_row;
+    uint32_t col_groups, nblocks, band_rows;
+    int s_vec8, s_row_vec4;
+};
+
 template <int HAD, int RND, int MODE>
-__global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t rows,
-                                                            int64_t cols, int64_t ld, uint32_t sign_mask,
-                                                            RngKey key, uint8_t *__restrict__ q,
-                                                            uint8_t *__restrict__ s, int s_vec8,
-                                                            uint32_t col_groups, uint8_t *__restrict__ q_row,
-                                                            uint8_t *__restrict__ s_row, int s_row_vec4,
-                                                            uint32_t band_rows)
+__global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, const TileJob job1,
+                                                            uint32_t sign_mask, RngKey key)
 {
+    const bool second = blockIdx.x >= job0.nblocks;  // uniform: everything below is selected per workgroup
+    const uint16_t *__restrict__ x = second ? job1.x : job0.x;
+    const int64_t rows = second ? job1.rows : job0.rows, cols = second ? job1.cols : job0.cols;
+    const int64_t ld = second ? job1.ld : job0.ld;
+    uint8_t *__restrict__ q = second ? job1.q : job0.q;
+    uint8_t *__restrict__ s = second ? job1.s : job0.s;
+    uint8_t *__restrict__ q_row = second ? job1.q_row : job0.q_row;
+    uint8_t *__restrict__ s_row = second ? job1.s_row : job0.s_row;
+    const uint32_t col_groups = second ? job1.col_groups : job0.col_groups;
+    const uint32_t nb = second ? job1.nblocks : job0.nblocks;
+    const uint32_t band_rows = second ? job1.band_rows : job0.band_rows;
+    const int s_vec8 = second ? job1.s_vec8 : job0.s_vec8, s_row_vec4 = second ? job1.s_row_vec4 : job0.s_row_vec4;
+    const uint32_t bid = blockIdx.x - (second ? job0.nblocks : 0u);
+
     constexpr bool PARK = (MODE != MODE_COLS);
     constexpr int LDS_BYTES = (PARK && LDS_RAW_BYTES > LDS_Q_BYTES + LDS_S_BYTES) ? LDS_RAW_BYTES
                                                                                   : LDS_Q_BYTES + LDS_S_BYTES;
@@ -277,12 +296,12 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const uint16_t *__re
     // so small that a CU sees only a few tiles, which keep the plain order band_rows = 0).
     uint32_t by, bx;
     if (band_rows == 0) {
-        by = blockIdx.x / col_groups;
-        bx = blockIdx.x - by * col_groups;
+        by = bid / col_groups;
+        bx = bid - by * col_groups;
     } else {
-        const uint32_t nb = gridDim.x, xcd = blockIdx.x & 7, per = nb >> 3, rem = nb & 7;
+        const uint32_t xcd = bid & 7, per = nb >> 3, rem = nb & 7;
         const uint32_t start = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-        const uint32_t lb = start + (blockIdx.x >> 3);
+        const uint32_t lb = start + (bid >> 3);
         const uint32_t row_groups = nb / col_groups, span = band_rows * col_groups;
         const uint32_t band = lb / span, in = lb - band * span;
         const uint32_t left = row_groups - band * band_rows, gm = left < band_rows ? left : band_rows;
@@ -439,26 +458,50 @@ hipError_t launch_rows_h(const QuantArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int HAD, int MODE>
-hipError_t launch_cols_h(const QuantArgs &a, hipStream_t st)
+template <int MODE>
+TileJob make_job(const QuantArgs &a)
 {
     const int64_t nrb = a.rows / 32;
-    // 1-D grid, column groups fastest: neighbouring workgroups read neighbouring memory
-    const uint32_t col_groups = (uint32_t)((a.cols + CT_COLS - 1) / CT_COLS);
-    dim3 grid((unsigned)(col_groups * ((nrb + CT_RB - 1) / CT_RB)));
+    TileJob j;
+    j.x = a.x; j.rows = a.rows; j.cols = a.cols; j.ld = a.ld;
+    j.q = a.q; j.s = a.s; j.q_row = a.q_row; j.s_row = a.s_row;
+    // column groups fastest: neighbouring workgroups read neighbouring memory
+    j.col_groups = (uint32_t)((a.cols + CT_COLS - 1) / CT_COLS);
+    j.nblocks = (uint32_t)(j.col_groups * ((nrb + CT_RB - 1) / CT_RB));
+    j.band_rows = j.nblocks < 2048 ? 0u : (MODE == MODE_COLS ? 16u : 2u);
+    j.s_vec8 = ((nrb % 8) == 0) && ((reinterpret_cast<uintptr_t>(a.s) % 8) == 0);
+    j.s_row_vec4 = MODE != MODE_COLS && a.s_row != nullptr && (((a.cols / 32) % 4) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
+    return j;
+}
+
+// b == nullptr: one tensor.  Otherwise both tensors in one launch (same rotation, rounding and seed).
+template <int HAD, int MODE>
+hipError_t launch_cols_h(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
+{
+    const TileJob j0 = make_job<MODE>(a);
+    TileJob j1 = j0;
+    j1.nblocks = 0;
+    if (b) j1 = make_job<MODE>(*b);
+    dim3 grid(j0.nblocks + j1.nblocks);
     const RngKey key = make_key(a.seed);
     const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
-    const int s_vec8 = ((nrb % 8) == 0) && ((reinterpret_cast<uintptr_t>(a.s) % 8) == 0);
-    const uint32_t band_rows = grid.x < 2048 ? 0u : (MODE == MODE_COLS ? 16u : 2u);
-    const int s_row_vec4 = MODE != MODE_COLS && a.s_row != nullptr && (((a.cols / 32) % 4) == 0) &&
-                           ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
     if (a.rounding == RND_RNE)
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, MODE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
-                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4, band_rows);
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask, key);
     else
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, MODE>), grid, dim3(512), 0, st, a.x, a.rows, a.cols,
-                           a.ld, sign_mask, key, a.q, a.s, s_vec8, col_groups, a.q_row, a.s_row, s_row_vec4, band_rows);
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask, key);
     return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_cols_mode(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
+{
+    switch (a.hadamard) {
+        case HAD_NONE: return launch_cols_h<HAD_NONE, MODE>(a, b, st);
+        case HAD_DET: return launch_cols_h<HAD_DET, MODE>(a, b, st);
+        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE>(a, b, st);
+        default: return launch_cols_h<HAD_DET16, MODE>(a, b, st);
+    }
 }
 
 }  // namespace
@@ -473,34 +516,16 @@ hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st)
     }
 }
 
-hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st)
+hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st) { return launch_cols_mode<MODE_COLS>(a, nullptr, st); }
+
+hipError_t launch_quantize_dual(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
 {
-    switch (a.hadamard) {
-        case HAD_NONE: return launch_cols_h<HAD_NONE, MODE_COLS>(a, st);
-        case HAD_DET: return launch_cols_h<HAD_DET, MODE_COLS>(a, st);
-        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE_COLS>(a, st);
-        default: return launch_cols_h<HAD_DET16, MODE_COLS>(a, st);
-    }
+    return launch_cols_mode<MODE_DUAL>(a, b, st);
 }
 
-hipError_t launch_quantize_dual(const QuantArgs &a, hipStream_t st)
+hipError_t launch_quantize_2d(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
 {
-    switch (a.hadamard) {
-        case HAD_NONE: return launch_cols_h<HAD_NONE, MODE_DUAL>(a, st);
-        case HAD_DET: return launch_cols_h<HAD_DET, MODE_DUAL>(a, st);
-        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE_DUAL>(a, st);
-        default: return launch_cols_h<HAD_DET16, MODE_DUAL>(a, st);
-    }
-}
-
-hipError_t launch_quantize_2d(const QuantArgs &a, hipStream_t st)
-{
-    switch (a.hadamard) {
-        case HAD_NONE: return launch_cols_h<HAD_NONE, MODE_2D>(a, st);
-        case HAD_DET: return launch_cols_h<HAD_DET, MODE_2D>(a, st);
-        case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE_2D>(a, st);
-        default: return launch_cols_h<HAD_DET16, MODE_2D>(a, st);
-    }
+    return launch_cols_mode<MODE_2D>(a, b, st);
 }
 
 }  // namespace mxfp4

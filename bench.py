@@ -51,8 +51,96 @@ def event_time_ms(fn, iters, torch):
     return start.elapsed_time(stop) / iters
 
 
+def other_config(args, torch, mx, synth) -> int:
+    """Timing of the benchmark configurations other than the headline one (1, 3, 4, 5): one JSON line each,
+    same conventions (inputs resident, rotation and quantisation inside the timed region)."""
+    dev = torch.device("cuda:0")
+
+    def time_calls(fn):
+        for _ in range(max(args.warmup // 5, 3)):
+            fn()
+        torch.cuda.synchronize()
+        n = max(args.steps // 10, 5)
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    def layer(Ml, Kl, Nl, had, rnd, x, w, dy, stages="fdw"):
+        cfg = mx.make_cfg(had, rnd, 2024, y_dtype=mx.OUT_BF16, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32)
+        ws_f = torch.empty(mx.mxfp4_linear_workspace_bytes(Ml, Nl, Kl, cfg, False), dtype=torch.uint8, device=dev)
+        ws_b = torch.empty(mx.mxfp4_linear_workspace_bytes(Ml, Nl, Kl, cfg, True), dtype=torch.uint8, device=dev)
+        y = torch.empty((Ml, Nl), dtype=torch.bfloat16, device=dev)
+        dx = torch.empty((Ml, Kl), dtype=torch.bfloat16, device=dev)
+        dw = torch.empty((Nl, Kl), dtype=torch.float32, device=dev)
+        if stages == "f":
+            return time_calls(lambda: mx.mxfp4_linear_fwd(x, w, cfg, y=y, workspace=ws_f)), 1
+        if stages == "w":
+            return time_calls(lambda: mx.mxfp4_linear_bwd(dy, x, None, cfg, dw=dw, need_dx=False, workspace=ws_b)), 1
+        saved = torch.empty(mx.mxfp4_linear_saved_bytes(Ml, Nl, Kl), dtype=torch.uint8, device=dev)
+
+        def both():
+            mx.mxfp4_linear_fwd_save(x, w, cfg, y=y, workspace=ws_f, saved=saved)
+            mx.mxfp4_linear_bwd_saved(dy, saved, Kl, cfg, dx=dx, dw=dw, workspace=ws_b)
+        return time_calls(both), 3
+
+    rows = []
+    if args.config == 1:
+        x = synth.normal(256, 512, 1.0, 0, synth.STREAM_X).to(dev)
+        w = synth.normal(512, 512, 0.02, 0, synth.STREAM_W).to(dev)
+        ms, g = layer(256, 512, 512, mx.HAD_NONE, mx.RNE, x, w, None, "f")
+        rows.append(("fprop 256x512x512 no-H RNE", ms, g * 2.0 * 256 * 512 * 512))
+        workload = "config 1: single linear Fprop, M=256 K=512 N=512, no rotation, RNE (launch-latency bound)"
+    elif args.config == 3:
+        for name, Kl, Nl, sd in (("gate/up", 4096, 28672, 0), ("down", 14336, 4096, 1)):
+            x = synth.normal_with_outlier_channels(8192, Kl, sd, synth.STREAM_X).to(dev)
+            w = synth.normal(Nl, Kl, 0.02, sd, synth.STREAM_W).to(dev)
+            dy = synth.normal(8192, Nl, 1e-3, sd, synth.STREAM_DY).to(dev)
+            for had, hn in ((mx.HAD_DET, "H32"), (mx.HAD_NONE, "no-H")):
+                ms, g = layer(8192, Kl, Nl, had, mx.RNE, x, w, dy)
+                rows.append((f"{name} {hn} fwd+bwd", ms, g * 2.0 * 8192 * Kl * Nl))
+            del x, w, dy
+        workload = "config 3: Llama-3.1-8B MLP (gate/up K=4096 N=28672, down K=14336 N=4096), M=8192, outlier channels"
+    elif args.config == 4:
+        Ml, Nl, Kl = 16384, 4096, 14336
+        dy = synth.student_t3(Ml, Nl, 1e-3, 0, synth.STREAM_DY).to(dev)
+        x = synth.normal(Ml, Kl, 1.0, 0, synth.STREAM_X).to(dev)
+        for had, rnd, nm in ((mx.HAD_DET, mx.RNE, "det-H RNE"), (mx.HAD_RANDSIGN, mx.RNE, "random-sign-H RNE"),
+                             (mx.HAD_NONE, mx.SR, "no-H SR")):
+            ms, g = layer(Ml, Kl, Nl, had, rnd, x, None, dy, "w")
+            rows.append((f"wgrad {nm}", ms, g * 2.0 * Ml * Kl * Nl))
+        workload = "config 4: Wgrad stress, dW[4096,14336] = dY^T X over M=16384 tokens, both operands column-wise"
+    else:
+        for name, Kl, Nl in (("q", 4096, 4096), ("k", 4096, 1024), ("v", 4096, 1024), ("o", 4096, 4096),
+                             ("gate", 4096, 14336), ("up", 4096, 14336), ("down", 14336, 4096)):
+            x = synth.normal(8192, Kl, 1.0, 5, synth.STREAM_X).to(dev)
+            w = synth.normal(Nl, Kl, 0.02, 5, synth.STREAM_W).to(dev)
+            dy = synth.normal(8192, Nl, 1e-3, 5, synth.STREAM_DY).to(dev)
+            ms, g = layer(8192, Kl, Nl, mx.HAD_DET, mx.RNE, x, w, dy)
+            rows.append((f"{name} K={Kl} N={Nl} fwd+bwd", ms, g * 2.0 * 8192 * Kl * Nl))
+            del x, w, dy
+        workload = "config 5: the 7 linears of one Llama-3.1-8B decoder layer, M=8192, det-H32 RNE, fwd+bwd (21 GEMMs)"
+    total_ms = sum(r[1] for r in rows)
+    total_flop = sum(r[2] for r in rows)
+    out = {
+        "metric": "mxfp4_linear_gemm_tflops_incl_hadamard_quantize",
+        "value": round(total_flop / (total_ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": max(args.steps // 10, 5), "warmup": max(args.warmup // 5, 3), "ms_per_step": round(total_ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp4", "data": "synthetic",
+        "config": {"workload": workload},
+        "pct_of_fp4_peak_incl_quant": round(100.0 * total_flop / (total_ms * 1e-3) / 1e12 / PEAK_FP4_TFLOPS, 2),
+        "parts": [{"what": n, "ms": round(ms, 4), "tflops_incl_quant": round(f / (ms * 1e-3) / 1e12, 1)}
+                  for n, ms, f in rows],
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="benchmark configuration; 2 (the default) is the headline workload with the full report")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
@@ -77,6 +165,8 @@ def main() -> int:
     mx.lib()  # fail loudly now if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.config != 2:
+        return other_config(args, torch, mx, synth)
 
     x_cpu = synth.normal(M, K, 1.0, 0, synth.STREAM_X)
     w_cpu = synth.normal(N, K, 0.02, 0, synth.STREAM_W)

@@ -294,6 +294,25 @@ static int quantize_operand_pair(const mxfp4_linear_cfg *cfg, const void *x0, in
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
+// Dgrad and Wgrad of one layer: two GEMMs on the same stream that do not depend on each other.
+static int gemm_pair(const GemmArgs &g0, int dt0, const GemmArgs &g1, int dt1, void *hip_stream)
+{
+    int rc = check_gemm(g0.aq, g0.as, g0.bq, g0.bs, g0.Ra, g0.Rb, g0.C, g0.out, g0.ld, dt0, g0.accumulate);
+    if (rc > 0) return rc;
+    int rc1 = check_gemm(g1.aq, g1.as, g1.bq, g1.bs, g1.Ra, g1.Rb, g1.C, g1.out, g1.ld, dt1, g1.accumulate);
+    if (rc1 > 0) return rc1;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipSuccess;
+    if (rc < 0 && rc1 < 0)
+        e = launch_gemm_pair(g0, g1, st);
+    else if (rc < 0)
+        e = launch_gemm(g0, st);
+    else if (rc1 < 0)
+        e = launch_gemm(g1, st);
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
 size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd)
 {
     (void)cfg;
@@ -362,17 +381,17 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
     if (dx) {
         rc = quantize_operand(cfg, w, N, K, nullptr, nullptr, ws + L.wtq, ws + L.wts, hip_stream);
         if (rc != MXFP4_OK) return rc;
-        rc = mxfp4_gemm(ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
-        if (rc != MXFP4_OK) return rc;
     }
     if (dw) {
         rc = quantize_operand(cfg, x, M, K, nullptr, nullptr, ws + L.xtq, ws + L.xts, hip_stream);
         if (rc != MXFP4_OK) return rc;
-        rc = mxfp4_gemm(ws + L.gtq, ws + L.gts, ws + L.xtq, ws + L.xts, N, K, M, dw, K, cfg->dw_dtype,
-                        cfg->dw_accumulate, hip_stream);
-        if (rc != MXFP4_OK) return rc;
     }
-    return MXFP4_OK;
+    const GemmArgs gd{ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0};
+    const GemmArgs gw{ws + L.gtq, ws + L.gts, ws + L.xtq, ws + L.xts, N, K, M, dw, K,
+                      cfg->dw_dtype == MXFP4_OUT_FP32, cfg->dw_accumulate};
+    if (dx && dw) return gemm_pair(gd, cfg->dx_dtype, gw, cfg->dw_dtype, hip_stream);
+    if (dx) return mxfp4_gemm(gd.aq, gd.as, gd.bq, gd.bs, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
+    return mxfp4_gemm(gw.aq, gw.as, gw.bq, gw.bs, N, K, M, dw, K, cfg->dw_dtype, cfg->dw_accumulate, hip_stream);
 }
 
 size_t mxfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K)
@@ -431,16 +450,12 @@ int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes
     rc = quantize_operand(cfg, dy, M, N, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
                           dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    if (dx) {
-        rc = mxfp4_gemm(ws + L.gq, ws + L.gs, sv + S.wtq, sv + S.wts, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
-        if (rc != MXFP4_OK) return rc;
-    }
-    if (dw) {
-        rc = mxfp4_gemm(ws + L.gtq, ws + L.gts, sv + S.xtq, sv + S.xts, N, K, M, dw, K, cfg->dw_dtype,
-                        cfg->dw_accumulate, hip_stream);
-        if (rc != MXFP4_OK) return rc;
-    }
-    return MXFP4_OK;
+    const GemmArgs gd{ws + L.gq, ws + L.gs, sv + S.wtq, sv + S.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0};
+    const GemmArgs gw{ws + L.gtq, ws + L.gts, sv + S.xtq, sv + S.xts, N, K, M, dw, K,
+                      cfg->dw_dtype == MXFP4_OUT_FP32, cfg->dw_accumulate};
+    if (dx && dw) return gemm_pair(gd, cfg->dx_dtype, gw, cfg->dw_dtype, hip_stream);
+    if (dx) return mxfp4_gemm(gd.aq, gd.as, gd.bq, gd.bs, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
+    return mxfp4_gemm(gw.aq, gw.as, gw.bq, gw.bs, N, K, M, dw, K, cfg->dw_dtype, cfg->dw_accumulate, hip_stream);
 }
 
 }  // extern "C"

@@ -178,16 +178,16 @@ struct TileSrc {
     int64_t m0, n0;
 };
 
+// The whole tiled GEMM as seen by one workgroup: `wg` of `nwg` workgroups share the problem (the ids are
+// virtual: a launch may run two problems side by side on disjoint sets of CUs).  smem: the workgroup's
+// LDS_BYTES of LDS, lds0 its LDS address.
 template <bool OUT_FP32, bool ACC>
-__global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__restrict__ aq,
-                                                           const uint8_t *__restrict__ as,
-                                                           const uint8_t *__restrict__ bq,
-                                                           const uint8_t *__restrict__ bs, int64_t C,
-                                                           void *__restrict__ out, int64_t ld, int tiles_m,
-                                                           int tiles_n)
+__device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, const uint8_t *__restrict__ as,
+                                               const uint8_t *__restrict__ bq, const uint8_t *__restrict__ bs,
+                                               int64_t C, void *__restrict__ out, int64_t ld, int tiles_m,
+                                               int tiles_n, const uint32_t wg, const uint32_t nwg,
+                                               uint8_t *const smem, const uint32_t lds0)
 {
-    __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -201,8 +201,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
     // their number, so the tiles in flight on one XCD are consecutive in the sequence, and the
     // sequence goes through the tile grid in groups of GROUP_M tile rows: those tiles share
     // A and B panels in the XCD's L2.
-    const int T = tiles_m * tiles_n, G = (int)gridDim.x;
-    const int xcd = blockIdx.x & 7, lw = blockIdx.x >> 3;
+    const int T = tiles_m * tiles_n, G = (int)nwg;
+    const int xcd = wg & 7, lw = wg >> 3;
     const int nwg_x = (G - xcd + 7) >> 3;                      // workgroups living on this XCD
     const int per = T >> 3, rem = T & 7;
     const int count_x = per + (xcd < rem ? 1 : 0);             // tiles owned by this XCD
@@ -484,31 +484,71 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const uint8_t *__rest
 #undef MXFP4_16
 }
 
+struct TileGemm {
+    const uint8_t *aq, *as, *bq, *bs;
+    int64_t C;
+    void *out;
+    int64_t ld;
+    int tiles_m, tiles_n;
+};
+
+template <bool OUT_FP32, bool ACC>
+__global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const TileGemm p)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    gemm_tile_body<OUT_FP32, ACC>(p.aq, p.as, p.bq, p.bs, p.C, p.out, p.ld, p.tiles_m, p.tiles_n, blockIdx.x,
+                                  gridDim.x, smem, lds0);
+}
+
+// Two independent GEMMs in one launch of 256 workgroups (Dgrad and Wgrad of one layer): on every XCD the
+// first n0 of its 32 workgroups work on p0, the others on p1, each set walking its own problem's tiles.
+// With the CUs split in proportion to the work both finish together, where one after the other each
+// would end on a partly filled round of tiles.
+template <bool OUT0, bool OUT1, bool ACC1>
+__global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p0, const TileGemm p1, const int n0)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    const uint32_t xcd = blockIdx.x & 7, lw = blockIdx.x >> 3;
+    if (lw < (uint32_t)n0)
+        gemm_tile_body<OUT0, false>(p0.aq, p0.as, p0.bq, p0.bs, p0.C, p0.out, p0.ld, p0.tiles_m, p0.tiles_n,
+                                    lw * 8 + xcd, (uint32_t)n0 * 8, smem, lds0);
+    else
+        gemm_tile_body<OUT1, ACC1>(p1.aq, p1.as, p1.bq, p1.bs, p1.C, p1.out, p1.ld, p1.tiles_m, p1.tiles_n,
+                                   (lw - n0) * 8 + xcd, (uint32_t)(32 - n0) * 8, smem, lds0);
+}
+
 }  // namespace
+
+// the tiled kernel wants whole 256 x 256 tiles, K in whole 512s (at least 1024: scale bytes are
+// fetched 32 per row, 16-byte aligned), and 16-byte aligned rows everywhere
+static bool tile_eligible(const GemmArgs &g)
+{
+    return g.C >= 1024 && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.C % 512) == 0 && (g.ld % 8) == 0 &&
+           (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 && (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 &&
+           (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) && g.C < (int64_t(1) << 31);
+}
+
+static TileGemm tile_args(const GemmArgs &g)
+{
+    return TileGemm{g.aq, g.as, g.bq, g.bs, g.C, g.out, g.ld, (int)(g.Ra / TILE), (int)(g.Rb / TILE)};
+}
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
 {
-    // the tiled kernel wants whole 256 x 256 tiles, K in whole 512s (at least 1024: scale bytes are
-    // fetched 32 per row, 16-byte aligned), and 16-byte aligned rows everywhere
-    const bool tiled = g.C >= 1024 && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.C % 512) == 0 &&
-                       (g.ld % 8) == 0 && (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 &&
-                       (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 && (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) &&
-                       g.C < (int64_t(1) << 31);
-    if (tiled) {
-        const int tiles_m = (int)(g.Ra / TILE), tiles_n = (int)(g.Rb / TILE);
+    if (tile_eligible(g)) {
+        const TileGemm p = tile_args(g);
         // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
-        const int T = tiles_m * tiles_n;
+        const int T = p.tiles_m * p.tiles_n;
         dim3 grid((unsigned)(T < NUM_CUS ? T : NUM_CUS));
         if (g.out_fp32) {
             if (g.accumulate)
-                hipLaunchKernelGGL((gemm_tile_kernel<true, true>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs,
-                                   g.C, g.out, g.ld, tiles_m, tiles_n);
+                hipLaunchKernelGGL((gemm_tile_kernel<true, true>), grid, dim3(256), 0, st, p);
             else
-                hipLaunchKernelGGL((gemm_tile_kernel<true, false>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs,
-                                   g.C, g.out, g.ld, tiles_m, tiles_n);
+                hipLaunchKernelGGL((gemm_tile_kernel<true, false>), grid, dim3(256), 0, st, p);
         } else {
-            hipLaunchKernelGGL((gemm_tile_kernel<false, false>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs,
-                               g.C, g.out, g.ld, tiles_m, tiles_n);
+            hipLaunchKernelGGL((gemm_tile_kernel<false, false>), grid, dim3(256), 0, st, p);
         }
         return hipGetLastError();
     }
@@ -525,6 +565,40 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
                            g.Rb, g.C, g.out, g.ld);
     }
     return hipGetLastError();
+}
+
+// g0 (no accumulation) and g1 on the same stream, no dependence between them.  Side by side in one launch
+// when both fit the tiled kernel and together fill the chip; otherwise one after the other.
+hipError_t launch_gemm_pair(const GemmArgs &g0, const GemmArgs &g1, hipStream_t st)
+{
+    const bool side_by_side = !g0.accumulate && tile_eligible(g0) && tile_eligible(g1);
+    if (side_by_side) {
+        const TileGemm p0 = tile_args(g0), p1 = tile_args(g1);
+        const int64_t t0 = (int64_t)p0.tiles_m * p0.tiles_n, t1 = (int64_t)p1.tiles_m * p1.tiles_n;
+        const double w0 = (double)t0 * (double)g0.C, w1 = (double)t1 * (double)g1.C;
+        int n0 = (int)(32.0 * w0 / (w0 + w1) + 0.5);  // workgroups per XCD for g0, in proportion to the work
+        n0 = n0 < 1 ? 1 : (n0 > 31 ? 31 : n0);
+        // worth it only if both shares have enough tiles to keep their CUs busy
+        if (t0 >= (int64_t)n0 * 8 && t1 >= (int64_t)(32 - n0) * 8) {
+            dim3 grid(NUM_CUS);
+#define MXFP4_PAIR(O0, O1, A1) \
+    hipLaunchKernelGGL((gemm_tile_pair_kernel<O0, O1, A1>), grid, dim3(256), 0, st, p0, p1, n0)
+            if (g0.out_fp32) {
+                if (!g1.out_fp32) MXFP4_PAIR(true, false, false);
+                else if (g1.accumulate) MXFP4_PAIR(true, true, true);
+                else MXFP4_PAIR(true, true, false);
+            } else {
+                if (!g1.out_fp32) MXFP4_PAIR(false, false, false);
+                else if (g1.accumulate) MXFP4_PAIR(false, true, true);
+                else MXFP4_PAIR(false, true, false);
+            }
+#undef MXFP4_PAIR
+            return hipGetLastError();
+        }
+    }
+    hipError_t e = launch_gemm(g0, st);
+    if (e != hipSuccess) return e;
+    return launch_gemm(g1, st);
 }
 
 }  // namespace mxfp4

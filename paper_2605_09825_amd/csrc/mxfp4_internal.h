@@ -37,5 +37,7 @@ struct GemmArgs {
 };
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);
+// two GEMMs that do not depend on each other (g0.accumulate must be 0); may share one launch
+hipError_t launch_gemm_pair(const GemmArgs &g0, const GemmArgs &g1, hipStream_t st);
 
 }  // namespace mxfp4

@@ -535,23 +535,8 @@ static TileGemm tile_args(const GemmArgs &g)
     return TileGemm{g.aq, g.as, g.bq, g.bs, g.C, g.out, g.ld, (int)(g.Ra / TILE), (int)(g.Rb / TILE)};
 }
 
-hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
+static hipError_t launch_any(const GemmArgs &g, hipStream_t st)
 {
-    if (tile_eligible(g)) {
-        const TileGemm p = tile_args(g);
-        // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
-        const int T = p.tiles_m * p.tiles_n;
-        dim3 grid((unsigned)(T < NUM_CUS ? T : NUM_CUS));
-        if (g.out_fp32) {
-            if (g.accumulate)
-                hipLaunchKernelGGL((gemm_tile_kernel<true, true>), grid, dim3(256), 0, st, p);
-            else
-                hipLaunchKernelGGL((gemm_tile_kernel<true, false>), grid, dim3(256), 0, st, p);
-        } else {
-            hipLaunchKernelGGL((gemm_tile_kernel<false, false>), grid, dim3(256), 0, st, p);
-        }
-        return hipGetLastError();
-    }
     dim3 grid((unsigned)((g.Ra + 63) / 64), (unsigned)((g.Rb + 63) / 64));
     if (g.out_fp32) {
         if (g.accumulate)
@@ -565,6 +550,62 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
                            g.Rb, g.C, g.out, g.ld);
     }
     return hipGetLastError();
+}
+
+static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
+{
+    const TileGemm p = tile_args(g);
+    // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
+    const int T = p.tiles_m * p.tiles_n;
+    dim3 grid((unsigned)(T < NUM_CUS ? T : NUM_CUS));
+    if (g.out_fp32) {
+        if (g.accumulate)
+            hipLaunchKernelGGL((gemm_tile_kernel<true, true>), grid, dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((gemm_tile_kernel<true, false>), grid, dim3(256), 0, st, p);
+    } else {
+        hipLaunchKernelGGL((gemm_tile_kernel<false, false>), grid, dim3(256), 0, st, p);
+    }
+    return hipGetLastError();
+}
+
+// rows r0.. (n of them) of A and columns c0.. (m of them) of B: the same problem on a sub-block of the output
+static GemmArgs sub_block(const GemmArgs &g, int64_t r0, int64_t n, int64_t c0, int64_t m)
+{
+    GemmArgs h = g;
+    const int64_t rowbytes = g.C / 2, nkb = g.C / 32;
+    h.aq = g.aq + r0 * rowbytes;
+    h.as = g.as + r0 * nkb;
+    h.bq = g.bq + c0 * rowbytes;
+    h.bs = g.bs + c0 * nkb;
+    h.Ra = n;
+    h.Rb = m;
+    h.out = static_cast<uint8_t *>(g.out) + (r0 * g.ld + c0) * (g.out_fp32 ? 4 : 2);
+    return h;
+}
+
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
+{
+    if (tile_eligible(g)) return launch_tiled(g, st);
+    // Ragged row counts: the 256-aligned interior goes through the tiled kernel, the right and bottom edge
+    // strips (less than one tile wide) through the any-shape kernel.
+    const int64_t ra = g.Ra / TILE * TILE, rb = g.Rb / TILE * TILE;
+    if (ra > 0 && rb > 0) {
+        const GemmArgs interior = sub_block(g, 0, ra, 0, rb);
+        // (the interior starts at offset 0 of every array, so it keeps the alignment of the whole problem; the
+        // any-shape kernel asks none of the strips' output pointers)
+        if (tile_eligible(interior)) {
+            hipError_t e = launch_tiled(interior, st);
+            if (e != hipSuccess) return e;
+            if (g.Rb > rb) {
+                e = launch_any(sub_block(g, 0, g.Ra, rb, g.Rb - rb), st);
+                if (e != hipSuccess) return e;
+            }
+            if (g.Ra > ra) e = launch_any(sub_block(g, ra, g.Ra - ra, 0, rb), st);
+            return e;
+        }
+    }
+    return launch_any(g, st);
 }
 
 // g0 (no accumulation) and g1 on the same stream, no dependence between them.  Side by side in one launch

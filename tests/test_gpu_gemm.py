@@ -49,6 +49,32 @@ def test_random_codes_fp32(shape):
     assert_close(got, want, absum)
 
 
+@pytest.mark.parametrize("shape", [(300, 520, 1024), (544, 784, 1536), (320, 256, 2048), (256, 257, 1024),
+                                   (1030, 513, 1024)])
+def test_ragged_rows_and_columns_around_whole_tiles(shape):
+    # row / column counts that leave edge strips beside a 256-aligned interior (different kernels write the
+    # interior and the strips): every output element once, nothing outside
+    Ra, Rb, C = shape
+    rng = np.random.default_rng(Ra * 5 + Rb * 11 + C)
+    aq, as_ = rand_operand(rng, Ra, C)
+    bq, bs = rand_operand(rng, Rb, C)
+    want, absum = oracle.gemm(aq, as_, bq, bs)
+    ld = Rb + 8 - Rb % 8 + 8  # padded rows: the padding must stay untouched
+    canvas = torch.full((Ra + 1, ld), 7.0, dtype=torch.float32, device="cuda:0")
+    mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out=canvas[:Ra, :Rb], out_dtype=mx.OUT_FP32)
+    torch.cuda.synchronize()
+    c = canvas.cpu().numpy()
+    assert_close(c[:Ra, :Rb], want, absum)
+    assert np.all(c[:Ra, Rb:] == 7.0) and np.all(c[Ra] == 7.0)
+    # accumulate on top, and bf16 output = RNE of the fp32 result
+    mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out=canvas[:Ra, :Rb], out_dtype=mx.OUT_FP32, accumulate=True)
+    b16 = run_gemm(aq, as_, bq, bs, out_dtype=mx.OUT_BF16)
+    torch.cuda.synchronize()
+    first = torch.from_numpy(c[:Ra, :Rb].copy())
+    assert torch.equal(canvas[:Ra, :Rb].cpu(), first + first)
+    assert torch.equal(b16.cpu(), first.to(torch.bfloat16))
+
+
 def test_wide_scale_range_and_exactness_on_small_sums():
     # one block per row (C = 32): at most 32 products, partial sums < 2^24 in units of the
     # smallest product: the fp32 result must be exact

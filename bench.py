@@ -33,10 +33,10 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 BYTES_PER_ELEM = 2.0 + 0.5 + 1.0 / 32.0  # bf16 read + packed codes + scale byte per element
 BYTES_PER_ELEM_DUAL = 2.0 + 2 * (0.5 + 1.0 / 32.0)  # one read, both quantisations written
 
-# Bytes crossing the L2's outward port per GEMM launch (mean of the three GEMMs), from the FETCH_SIZE and
+# Bytes crossing the L2's outward port per GEMM (mean of the three GEMMs of a step), from the FETCH_SIZE and
 # WRITE_SIZE runs summarised in profiles/qkv_traffic_counters.md (FETCH_SIZE x 2.0 after calibration
 # against a 256 MiB copy)
-GEMM_TRAFFIC_BYTES = 267.7e6
+GEMM_TRAFFIC_BYTES = 294.9e6
 
 
 def event_time_ms(fn, iters, torch):

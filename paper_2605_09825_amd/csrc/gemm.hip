@@ -435,15 +435,31 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
                                                        ((fh ^ ((r >> 4) & 1)) << 3)) = pk;
                             if (qd == 3) __builtin_amdgcn_sched_barrier(0);  // one 32x32 tile at a time
                         }
-                // 16 lanes x 16 bytes = one 256-byte row segment; 4 rows per instruction
+                // 16 lanes x 16 bytes = one 256-byte row segment; 4 rows per instruction.  Eight LDS reads are
+                // issued before the first store needs its data, so their latencies overlap; the row pointer
+                // is one per-lane base plus a scalar multiple of the leading dimension.
                 const int rl = lane >> 4, ch = lane & 15;
+                uint32_t roff[4];  // LDS offset of this lane's chunk in rows rl, 4 + rl, 8 + rl, 12 + rl
 #pragma unroll
-                for (int r4 = 0; r4 < 64; r4 += 4) {
-                    const int r = r4 + rl;
-                    v4i v = *reinterpret_cast<const v4i *>(epi + r * 256 + ((ch ^ (r & 15)) << 4));
-                    if ((r4 >> 4) & 1) v = (v4i){v.z, v.w, v.x, v.y};
-                    *reinterpret_cast<v4i *>(reinterpret_cast<uint16_t *>(out) + (row0 + pass * 64 + r) * ld + col0 +
-                                             ch * 8) = v;
+                for (int k = 0; k < 4; ++k) roff[k] = (uint32_t)((4 * k + rl) * 256 + ((ch ^ (4 * k + rl)) << 4));
+                uint16_t *obase = reinterpret_cast<uint16_t *>(out) + (row0 + pass * 64 + rl) * ld + col0 + ch * 8;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    v4i buf[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int r4 = (8 * h + u) * 4;
+                        buf[u] = *reinterpret_cast<const v4i *>(epi + (r4 & ~15) * 256 + roff[(r4 >> 2) & 3]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int r4 = (8 * h + u) * 4;
+                        v4i v = buf[u];
+                        if ((r4 >> 4) & 1) v = (v4i){v.z, v.w, v.x, v.y};
+                        *reinterpret_cast<v4i *>(obase + (int64_t)r4 * ld) = v;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         } else {
@@ -459,16 +475,27 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
                                   acc[pass][j][4 * qd + 3]};
                         if (qd == 3) __builtin_amdgcn_sched_barrier(0);
                     }
-                // 32 lanes x 16 bytes = one 512-byte row segment; 2 rows per instruction
+                // 32 lanes x 16 bytes = one 512-byte row segment; 2 rows per instruction; reads batched by
+                // eight as above
                 const int rl = lane >> 5, ch = lane & 31;
+                float *obase = reinterpret_cast<float *>(out) + (row0 + pass * 32 + rl) * ld + col0 + ch * 4;
 #pragma unroll
-                for (int r2 = 0; r2 < 32; r2 += 2) {
-                    const int r = r2 + rl;
-                    v4f v = *reinterpret_cast<const v4f *>(epi + r * 512 + ((ch ^ r) << 4));
-                    v4f *o = reinterpret_cast<v4f *>(reinterpret_cast<float *>(out) + (row0 + pass * 32 + r) * ld +
-                                                     col0 + ch * 4);
-                    if (ACC) v += *o;
-                    *o = v;
+                for (int h = 0; h < 2; ++h) {
+                    v4f buf[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int r = (8 * h + u) * 2 + rl;
+                        buf[u] = *reinterpret_cast<const v4f *>(epi + r * 512 + ((ch ^ r) << 4));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        v4f *o = reinterpret_cast<v4f *>(obase + (int64_t)((8 * h + u) * 2) * ld);
+                        v4f v = buf[u];
+                        if (ACC) v += *o;
+                        *o = v;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }

@@ -530,8 +530,10 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const TileGemm p)
 
 // Two independent GEMMs in one launch of 256 workgroups (Dgrad and Wgrad of one layer): on every XCD the
 // first n0 of its 32 workgroups work on p0, the others on p1, each set walking its own problem's tiles.
-// With the CUs split in proportion to the work both finish together, where one after the other each
-// would end on a partly filled round of tiles.
+// The CUs are split in proportion to the work, so both problems end on full rounds of tiles.  Measured on
+// the 8B shapes this only gains the dispatch gap between two launches (about 6 us): with half the chip idle
+// in a partly filled last round the busy half clocks higher under the power cap, and here each XCD's L2
+// holds panels of two problems (22 % more traffic beyond L2).
 template <bool OUT0, bool OUT1, bool ACC1>
 __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p0, const TileGemm p1, const int n0)
 {

@@ -23,6 +23,7 @@ _LIB = os.path.join(_HERE, "libmxfp4_oracle.so")
 AXIS_LAST, AXIS_FIRST = 0, 1
 HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16 = 0, 1, 2, 3
 RNE, SR = 0, 1
+FMT_E2M1, FMT_E4M3 = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -70,6 +71,19 @@ def lib() -> ctypes.CDLL:
         L.orc_quantize_2d.restype = ctypes.c_int
         L.orc_quantize_2d.argtypes = [u16p, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_uint64, u8p, u8p]
+        L.orc_e4m3_decode.restype = ctypes.c_double
+        L.orc_e4m3_decode.argtypes = [ctypes.c_uint]
+        L.orc_e4m3_encode_rne.restype = ctypes.c_uint
+        L.orc_e4m3_encode_rne.argtypes = [ctypes.c_double]
+        L.orc_e8m0_from_amax_bits_fp8.restype = ctypes.c_uint
+        L.orc_e8m0_from_amax_bits_fp8.argtypes = [ctypes.c_uint32]
+        L.orc_quantize_fp8.restype = ctypes.c_int
+        L.orc_quantize_fp8.argtypes = [u16p, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_uint64, u8p, u8p]
+        L.orc_gemm_fmt.restype = ctypes.c_int
+        L.orc_gemm_fmt.argtypes = [u8p, u8p, ctypes.c_int, u8p, u8p, ctypes.c_int, i64, i64, i64, f64p, f64p]
+        L.orc_gemm_at_fmt.restype = ctypes.c_int
+        L.orc_gemm_at_fmt.argtypes = [u8p, u8p, ctypes.c_int, u8p, u8p, ctypes.c_int, i64, i64, i64, i64p, i64p, i64,
+                                      f64p, f64p]
         L.orc_dequantize.restype = None
         L.orc_dequantize.argtypes = [u8p, u8p, i64, i64, f64p]
         L.orc_gemm.restype = ctypes.c_int
@@ -217,6 +231,72 @@ def gemm_at(aq, as_, bq, bs, ii, jj):
                            ii.size, _p(out, ctypes.c_double), _p(ab, ctypes.c_double))
     if rc != 0:
         raise RuntimeError(f"orc_gemm_at failed: {rc}")
+    return out, ab
+
+
+def e4m3_decode(code: int) -> float:
+    return float(lib().orc_e4m3_decode(int(code)))
+
+
+def e4m3_encode_rne(t: float) -> int:
+    return int(lib().orc_e4m3_encode_rne(float(t)))
+
+
+def e8m0_from_amax_bits_fp8(bits: int) -> int:
+    return int(lib().orc_e8m0_from_amax_bits_fp8(int(bits)))
+
+
+def quantize_fp8(x_bf16: np.ndarray, axis: int = AXIS_LAST, had: int = HAD_NONE,
+                 seed: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """MXFP8 (E4M3 elements): returns (q8 uint8 [R][C], s uint8 [R][C/32])."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2
+    assert x_bf16.strides[1] == 2 and x_bf16.strides[0] % 2 == 0
+    rows, cols = x_bf16.shape
+    ld = x_bf16.strides[0] // 2
+    R, C = (rows, cols) if axis == AXIS_LAST else (cols, rows)
+    if C % 32 != 0:
+        raise ValueError("contraction length must be a multiple of 32")
+    q = np.empty((R, C), dtype=np.uint8)
+    s = np.empty((R, C // 32), dtype=np.uint8)
+    rc = lib().orc_quantize_fp8(_p(x_bf16, ctypes.c_uint16), rows, cols, ld, axis, had, seed & (2**64 - 1),
+                                _p(q, ctypes.c_uint8), _p(s, ctypes.c_uint8))
+    if rc != 0:
+        raise RuntimeError(f"orc_quantize_fp8 failed: {rc}")
+    return q, s
+
+
+def _contraction_length(q: np.ndarray, fmt: int) -> int:
+    return q.shape[1] * (2 if fmt == FMT_E2M1 else 1)
+
+
+def gemm_fmt(aq, as_, afmt, bq, bs, bfmt):
+    """gemm() with each operand in its own element format; returns (out, absum)."""
+    aq, as_, bq, bs = (np.ascontiguousarray(t, dtype=np.uint8) for t in (aq, as_, bq, bs))
+    Ra, Rb, C = aq.shape[0], bq.shape[0], _contraction_length(aq, afmt)
+    assert _contraction_length(bq, bfmt) == C and as_.shape == (Ra, C // 32) and bs.shape == (Rb, C // 32)
+    out = np.empty((Ra, Rb), dtype=np.float64)
+    ab = np.empty((Ra, Rb), dtype=np.float64)
+    rc = lib().orc_gemm_fmt(_p(aq, ctypes.c_uint8), _p(as_, ctypes.c_uint8), afmt, _p(bq, ctypes.c_uint8),
+                            _p(bs, ctypes.c_uint8), bfmt, Ra, Rb, C, _p(out, ctypes.c_double),
+                            _p(ab, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"orc_gemm_fmt failed: {rc}")
+    return out, ab
+
+
+def gemm_at_fmt(aq, as_, afmt, bq, bs, bfmt, ii, jj):
+    aq, as_, bq, bs = (np.ascontiguousarray(t, dtype=np.uint8) for t in (aq, as_, bq, bs))
+    ii = np.ascontiguousarray(ii, dtype=np.int64)
+    jj = np.ascontiguousarray(jj, dtype=np.int64)
+    Ra, Rb, C = aq.shape[0], bq.shape[0], _contraction_length(aq, afmt)
+    assert _contraction_length(bq, bfmt) == C and ii.shape == jj.shape and ii.ndim == 1
+    out = np.empty(ii.shape, dtype=np.float64)
+    ab = np.empty(ii.shape, dtype=np.float64)
+    rc = lib().orc_gemm_at_fmt(_p(aq, ctypes.c_uint8), _p(as_, ctypes.c_uint8), afmt, _p(bq, ctypes.c_uint8),
+                               _p(bs, ctypes.c_uint8), bfmt, Ra, Rb, C, _p(ii, ctypes.c_int64),
+                               _p(jj, ctypes.c_int64), ii.size, _p(out, ctypes.c_double), _p(ab, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"orc_gemm_at_fmt failed: {rc}")
     return out, ab
 
 

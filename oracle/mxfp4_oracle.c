@@ -41,6 +41,7 @@
 enum { ORC_AXIS_LAST = 0, ORC_AXIS_FIRST = 1 };
 enum { ORC_HAD_NONE = 0, ORC_HAD_DET = 1, ORC_HAD_RANDSIGN = 2, ORC_HAD_DET16 = 3 };
 enum { ORC_RNE = 0, ORC_SR = 1 };
+enum { ORC_FMT_E2M1 = 0, ORC_FMT_E4M3 = 1 };
 
 /* ------------------------------------------------------------------------- */
 /* Counter-based random numbers (no state: a pure function of seed and index) */
@@ -148,6 +149,48 @@ unsigned orc_e2m1_encode_sr(double t, uint32_t r)
         if (E2M1_MAG[c] == mag) break;
     if (c == 8) abort(); /* cannot happen: mag is always on the grid */
     return (signbit(t) ? 8u : 0u) | c;
+}
+
+/* E4M3 (OCP 8-bit floating point, the MXFP8 element of the FP8 stages): 1 sign, 4
+ * exponent bits (bias 7), 3 mantissa bits; subnormals at exponent field 0; no
+ * infinities; the all-ones magnitude (0x7F) is NaN; largest finite 448. */
+double orc_e4m3_decode(unsigned code)
+{
+    unsigned e = (code >> 3) & 15u, m = code & 7u;
+    double mag;
+    if (e == 15u && m == 7u) return NAN;
+    mag = (e == 0u) ? ldexp((double)m, -9) : ldexp(1.0 + (double)m / 8.0, (int)e - 7);
+    return (code & 0x80u) ? -mag : mag;
+}
+
+/* Round-to-nearest, ties to the even mantissa, saturating at 448; never NaN.
+ * The sign bit is that of t, also for results of magnitude 0. */
+unsigned orc_e4m3_encode_rne(double t)
+{
+    double a = fabs(t);
+    unsigned best = 0;
+    double best_d = INFINITY;
+    if (a > 448.0) a = 448.0;
+    for (unsigned c = 0; c < 127u; ++c) { /* 0x7F is NaN */
+        double d = fabs(a - orc_e4m3_decode(c));
+        if (d < best_d || (d == best_d && (c & 1u) == 0)) {
+            best_d = d;
+            best = c;
+        }
+    }
+    return (signbit(t) ? 0x80u : 0u) | best;
+}
+
+/* E8M0 byte of an MXFP8 (E4M3) block: as orc_e8m0_from_amax_bits with the
+ * largest E4M3 exponent (8) in place of E2M1's (2). */
+unsigned orc_e8m0_from_amax_bits_fp8(uint32_t amax_bits)
+{
+    int e_b = (int)((amax_bits >> 23) & 0xFFu);
+    if (e_b == 255) return 0xFFu;
+    int byte = e_b - 8;
+    if (byte < 0) byte = 0;
+    if (byte > 254) byte = 254;
+    return (unsigned)byte;
 }
 
 /* E8M0 byte for a block whose largest magnitude has the fp32 bit pattern
@@ -326,6 +369,38 @@ int orc_quantize_2d(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, i
     return 0;
 }
 
+/* MXFP8 quantiser for the stages that stay in 8 bits (Table 1, "others FP8"):
+ * as orc_quantize with E4M3 elements, one byte each: q8[R][C], s[R][C/32];
+ * round-to-nearest-even only.  Returns 0, or 1 if C is not a multiple of 32. */
+int orc_quantize_fp8(const uint16_t *x, int64_t rows, int64_t cols, int64_t ld, int axis, int had, uint64_t seed,
+                     uint8_t *q8, uint8_t *s)
+{
+    int64_t R = (axis == ORC_AXIS_LAST) ? rows : cols;
+    int64_t C = (axis == ORC_AXIS_LAST) ? cols : rows;
+    if (C % MX_BLOCK != 0) return 1;
+    uint32_t sign_mask = orc_sign_mask(seed);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r) {
+        for (int64_t b = 0; b < C / MX_BLOCK; ++b) {
+            float v[MX_BLOCK];
+            for (int i = 0; i < MX_BLOCK; ++i) {
+                int64_t c = b * MX_BLOCK + i;
+                uint16_t h = (axis == ORC_AXIS_LAST) ? x[r * ld + c] : x[c * ld + r];
+                v[i] = orc_bf16_to_f32(h);
+            }
+            rotate_block(v, had, sign_mask);
+            unsigned sb = orc_e8m0_from_amax_bits_fp8(amax_bits_of(v, MX_BLOCK));
+            s[r * (C / MX_BLOCK) + b] = (uint8_t)sb;
+            for (int i = 0; i < MX_BLOCK; ++i) {
+                uint8_t code = 0;
+                if (sb != 0xFFu) code = (uint8_t)orc_e4m3_encode_rne(ldexp((double)v[i], 127 - (int)sb));
+                q8[r * C + b * MX_BLOCK + i] = code;
+            }
+        }
+    }
+    return 0;
+}
+
 /* Reconstructed values x_MX of eq. (1): code value times 2^(scale byte - 127).
  * A block whose scale byte is 0xFF decodes to NaN. */
 void orc_dequantize(const uint8_t *q, const uint8_t *s, int64_t R, int64_t C, double *out)
@@ -344,13 +419,19 @@ void orc_dequantize(const uint8_t *q, const uint8_t *s, int64_t R, int64_t C, do
 /* GEMM on quantised operands                                                 */
 /* ------------------------------------------------------------------------- */
 
-static void decode_row(const uint8_t *q, const uint8_t *s, int64_t r, int64_t C, double *dst)
+/* fmt: ORC_FMT_E2M1 (two codes per byte, q[R][C/2]) or ORC_FMT_E4M3 (one byte per element, q[R][C]) */
+static void decode_row_fmt(const uint8_t *q, const uint8_t *s, int fmt, int64_t r, int64_t C, double *dst)
 {
     for (int64_t c = 0; c < C; ++c) {
-        unsigned byte = q[r * (C / 2) + c / 2];
-        unsigned code = (c & 1) ? (byte >> 4) : (byte & 15u);
         unsigned sb = s[r * (C / MX_BLOCK) + c / MX_BLOCK];
-        dst[c] = (sb == 0xFFu) ? NAN : ldexp(orc_e2m1_decode(code), (int)sb - 127);
+        double val;
+        if (fmt == ORC_FMT_E4M3) {
+            val = orc_e4m3_decode(q[r * C + c]);
+        } else {
+            unsigned byte = q[r * (C / 2) + c / 2];
+            val = orc_e2m1_decode((c & 1) ? (byte >> 4) : (byte & 15u));
+        }
+        dst[c] = (sb == 0xFFu) ? NAN : ldexp(val, (int)sb - 127);
     }
 }
 
@@ -358,20 +439,30 @@ static void decode_row(const uint8_t *q, const uint8_t *s, int64_t r, int64_t C,
  * (every product is exact; only the running sum rounds).  absum, if not NULL,
  * receives sum_c |A[i][c]| |B[j][c]|, the yardstick of the GEMM tolerance.
  * A is [Ra][C], B is [Rb][C], both in the quantiser's output layout. */
+int orc_gemm_fmt(const uint8_t *aq, const uint8_t *as, int afmt, const uint8_t *bq, const uint8_t *bs, int bfmt,
+                 int64_t Ra, int64_t Rb, int64_t C, double *out, double *absum);
+
 int orc_gemm(const uint8_t *aq, const uint8_t *as, const uint8_t *bq, const uint8_t *bs, int64_t Ra, int64_t Rb,
              int64_t C, double *out, double *absum)
+{
+    return orc_gemm_fmt(aq, as, ORC_FMT_E2M1, bq, bs, ORC_FMT_E2M1, Ra, Rb, C, out, absum);
+}
+
+/* The same sum with each operand in its own element format (MXFP4 or MXFP8). */
+int orc_gemm_fmt(const uint8_t *aq, const uint8_t *as, int afmt, const uint8_t *bq, const uint8_t *bs, int bfmt,
+                 int64_t Ra, int64_t Rb, int64_t C, double *out, double *absum)
 {
     if (C % MX_BLOCK != 0) return 1;
     double *B = (double *)malloc(sizeof(double) * (size_t)Rb * (size_t)C);
     if (!B) return 2;
 #pragma omp parallel for schedule(static)
-    for (int64_t j = 0; j < Rb; ++j) decode_row(bq, bs, j, C, B + j * C);
+    for (int64_t j = 0; j < Rb; ++j) decode_row_fmt(bq, bs, bfmt, j, C, B + j * C);
 #pragma omp parallel
     {
         double *a = (double *)malloc(sizeof(double) * (size_t)C);
 #pragma omp for schedule(static)
         for (int64_t i = 0; i < Ra; ++i) {
-            decode_row(aq, as, i, C, a);
+            decode_row_fmt(aq, as, afmt, i, C, a);
             for (int64_t j = 0; j < Rb; ++j) {
                 const double *b = B + j * C;
                 double acc = 0.0, ab = 0.0;
@@ -391,8 +482,19 @@ int orc_gemm(const uint8_t *aq, const uint8_t *as, const uint8_t *bq, const uint
 }
 
 /* The same sum for n chosen output positions (ii[k], jj[k]) only. */
+int orc_gemm_at_fmt(const uint8_t *aq, const uint8_t *as, int afmt, const uint8_t *bq, const uint8_t *bs, int bfmt,
+                    int64_t Ra, int64_t Rb, int64_t C, const int64_t *ii, const int64_t *jj, int64_t n, double *out,
+                    double *absum);
+
 int orc_gemm_at(const uint8_t *aq, const uint8_t *as, const uint8_t *bq, const uint8_t *bs, int64_t Ra, int64_t Rb,
                 int64_t C, const int64_t *ii, const int64_t *jj, int64_t n, double *out, double *absum)
+{
+    return orc_gemm_at_fmt(aq, as, ORC_FMT_E2M1, bq, bs, ORC_FMT_E2M1, Ra, Rb, C, ii, jj, n, out, absum);
+}
+
+int orc_gemm_at_fmt(const uint8_t *aq, const uint8_t *as, int afmt, const uint8_t *bq, const uint8_t *bs, int bfmt,
+                    int64_t Ra, int64_t Rb, int64_t C, const int64_t *ii, const int64_t *jj, int64_t n, double *out,
+                    double *absum)
 {
     if (C % MX_BLOCK != 0) return 1;
     for (int64_t k = 0; k < n; ++k)
@@ -403,8 +505,8 @@ int orc_gemm_at(const uint8_t *aq, const uint8_t *as, const uint8_t *bq, const u
         double *b = (double *)malloc(sizeof(double) * (size_t)C);
 #pragma omp for schedule(dynamic, 16)
         for (int64_t k = 0; k < n; ++k) {
-            decode_row(aq, as, ii[k], C, a);
-            decode_row(bq, bs, jj[k], C, b);
+            decode_row_fmt(aq, as, afmt, ii[k], C, a);
+            decode_row_fmt(bq, bs, bfmt, jj[k], C, b);
             double acc = 0.0, ab = 0.0;
             for (int64_t c = 0; c < C; ++c) {
                 double p = a[c] * b[c];

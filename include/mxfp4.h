@@ -76,6 +76,12 @@ typedef enum {
     MXFP4_GEOM_2D = 1  /* one scale per 32 x 32 region; needs M, N, K all multiples of 32      */
 } mxfp4_geometry;
 
+/* Element format of a quantised operand. */
+typedef enum {
+    MXFP4_FMT_E2M1 = 0, /* MXFP4: two 4-bit codes per byte, q[R][C/2]                           */
+    MXFP4_FMT_E4M3 = 1  /* MXFP8: one OCP E4M3 byte per element, q[R][C]                        */
+} mxfp4_format;
+
 /* Recipe of one linear layer (one row of Table 1: stabiliser x rounding, all stages MXFP4). */
 typedef struct {
     int32_t hadamard;      /* mxfp4_hadamard, used for both operands of every GEMM             */
@@ -139,6 +145,25 @@ int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t 
 int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
                       int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
                       void *hip_stream);
+
+/*
+ * MXFP8 quantiser for the stages of the stage-wise recipe that stay in 8 bits (Table 1: "MXFP4 GEMMs
+ * (others FP8)").  As mxfp4_quantize with OCP E4M3 elements (bias 7, largest finite 448, no infinities):
+ * scale byte = clamp(biased exponent of the block maximum - 8, 0, 254); element = value * 2^-(byte-127)
+ * rounded to nearest even, saturating at +-448; round-to-nearest only.
+ *   q8_out uint8 [R][C], 16-byte aligned     s_out uint8 [R][C/32]
+ * axis, hadamard, seed, shapes and alignment rules as for mxfp4_quantize.
+ */
+int mxfp4_quantize_fp8(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int axis, int hadamard,
+                       uint64_t seed, void *q8_out, void *s_out, void *hip_stream);
+
+/*
+ * mxfp4_gemm with each operand in its own element format (mxfp4_format): the same block-scaled matrix
+ * instruction takes E2M1 and E4M3 operands in any combination.
+ */
+int mxfp4_gemm_fmt(const void *a_q, const void *a_s, int a_format, const void *b_q, const void *b_s, int b_format,
+                   int64_t R_a, int64_t R_b, int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate,
+                   void *hip_stream);
 
 /*
  * Block-scaled FP4 GEMM on quantised operands (the MXFP4 GEMM that replaces the FP8 GEMM of

@@ -21,8 +21,10 @@ HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16 = 0, 1, 2, 3
 RNE, SR = 0, 1
 OUT_BF16, OUT_FP32 = 0, 1
 GEOM_1D, GEOM_2D = 0, 1
+FMT_E2M1, FMT_E4M3 = 0, 1
 
-EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_gemm", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
+EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_quantize_fp8", "mxfp4_gemm",
+           "mxfp4_gemm_fmt", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
            "mxfp4_linear_fwd_save", "mxfp4_linear_bwd_saved", "mxfp4_linear_saved_bytes",
            "mxfp4_linear_saved_layout", "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout",
            "mxfp4_status_string")
@@ -57,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, u64, vp, vp, vp]
         L.mxfp4_quantize_dual.restype = ci
         L.mxfp4_quantize_dual.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp, vp, vp]
+        L.mxfp4_quantize_fp8.restype = ci
+        L.mxfp4_quantize_fp8.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp]
+        L.mxfp4_gemm_fmt.restype = ci
+        L.mxfp4_gemm_fmt.argtypes = [vp, vp, ci, vp, vp, ci, i64, i64, i64, vp, i64, ci, ci, vp]
         L.mxfp4_quantize_2d.restype = ci
         L.mxfp4_quantize_2d.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp, vp, vp]
         L.mxfp4_linear_fwd_save.restype = ci
@@ -160,19 +166,43 @@ def mxfp4_quantize_2d(x, hadamard: int = HAD_NONE, rounding: int = RNE, seed: in
     return ql, sl, qf, sf
 
 
-def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumulate: bool = False, stream=None):
-    """out[i][j] (+)= sum_c A[i][c] B[j][c] on canonical quantised operands (uint8 CUDA tensors)."""
+def mxfp4_quantize_fp8(x, axis: int = AXIS_LAST, hadamard: int = HAD_NONE, seed: int = 0, q=None, s=None,
+                       stream=None):
+    """MXFP8 (E4M3) quantisation of x [rows][cols]: returns (q8 [R][C], s [R][C/32])."""
     import torch
-    Ra, C = a_q.shape[0], a_q.shape[1] * 2
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and (x.numel() == 0 or x.stride(1) == 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, x.stride(0))
+    R, C = (rows, cols) if axis == AXIS_LAST else (cols, rows)
+    if q is None:
+        q = torch.empty((R, C), dtype=torch.uint8, device=x.device)
+    if s is None:
+        s = torch.empty((R, C // 32), dtype=torch.uint8, device=x.device)
+    _check("mxfp4_quantize_fp8", lib().mxfp4_quantize_fp8(_ptr(x), rows, cols, ld, axis, hadamard,
+                                                          seed & (2**64 - 1), _ptr(q), _ptr(s), _stream_ptr(stream)))
+    return q, s
+
+
+def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumulate: bool = False, stream=None,
+               a_format: int = FMT_E2M1, b_format: int = FMT_E2M1):
+    """out[i][j] (+)= sum_c A[i][c] B[j][c] on canonical quantised operands (uint8 CUDA tensors); with a format
+    other than E2M1 for either operand the call goes to mxfp4_gemm_fmt."""
+    import torch
+    Ra, C = a_q.shape[0], a_q.shape[1] * (2 if a_format == FMT_E2M1 else 1)
     Rb = b_q.shape[0]
-    assert b_q.shape[1] * 2 == C and a_q.is_contiguous() and b_q.is_contiguous()
+    assert b_q.shape[1] * (2 if b_format == FMT_E2M1 else 1) == C and a_q.is_contiguous() and b_q.is_contiguous()
     assert a_s.is_contiguous() and b_s.is_contiguous()
     if out is None:
         out = torch.empty((Ra, Rb), dtype=_out_dtype(out_dtype), device=a_q.device)
     assert out.dtype == _out_dtype(out_dtype) and (out.numel() == 0 or out.stride(1) == 1)
     ld = out.stride(0) if Ra > 1 else max(Rb, out.stride(0))
-    _check("mxfp4_gemm", lib().mxfp4_gemm(_ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), Ra, Rb, C, _ptr(out), ld,
-                                          out_dtype, int(accumulate), _stream_ptr(stream)))
+    if a_format == FMT_E2M1 and b_format == FMT_E2M1:
+        _check("mxfp4_gemm", lib().mxfp4_gemm(_ptr(a_q), _ptr(a_s), _ptr(b_q), _ptr(b_s), Ra, Rb, C, _ptr(out), ld,
+                                              out_dtype, int(accumulate), _stream_ptr(stream)))
+    else:
+        _check("mxfp4_gemm_fmt", lib().mxfp4_gemm_fmt(_ptr(a_q), _ptr(a_s), a_format, _ptr(b_q), _ptr(b_s), b_format,
+                                                      Ra, Rb, C, _ptr(out), ld, out_dtype, int(accumulate),
+                                                      _stream_ptr(stream)))
     return out
 
 

@@ -233,17 +233,40 @@ int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
-int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_s, int64_t R_a, int64_t R_b,
-               int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream)
+int mxfp4_quantize_fp8(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int axis, int hadamard,
+                       uint64_t seed, void *q8_out, void *s_out, void *hip_stream)
 {
+    int rc = check_quantize(x_bf16, rows, cols, ld_elems, axis, hadamard, MXFP4_RNE, q8_out, s_out);
+    if (rc >= 0) return rc;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    QuantArgs a{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, MXFP4_RNE, seed,
+                static_cast<uint8_t *>(q8_out), static_cast<uint8_t *>(s_out)};
+    hipError_t e = launch_quantize_fp8(a, axis == MXFP4_AXIS_FIRST, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
+int mxfp4_gemm_fmt(const void *a_q, const void *a_s, int a_format, const void *b_q, const void *b_s, int b_format,
+                   int64_t R_a, int64_t R_b, int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate,
+                   void *hip_stream)
+{
+    if ((a_format != MXFP4_FMT_E2M1 && a_format != MXFP4_FMT_E4M3) ||
+        (b_format != MXFP4_FMT_E2M1 && b_format != MXFP4_FMT_E4M3))
+        return MXFP4_EINVAL;
     int rc = check_gemm(a_q, a_s, b_q, b_s, R_a, R_b, C, out, ld_out, out_dtype, accumulate);
     if (rc >= 0) return rc;
     if (!device_ok()) return MXFP4_EDEVICE;
     GemmArgs g{static_cast<const uint8_t *>(a_q), static_cast<const uint8_t *>(a_s),
                static_cast<const uint8_t *>(b_q), static_cast<const uint8_t *>(b_s),
-               R_a, R_b, C, out, ld_out, out_dtype == MXFP4_OUT_FP32, accumulate};
+               R_a, R_b, C, out, ld_out, out_dtype == MXFP4_OUT_FP32, accumulate, a_format, b_format};
     hipError_t e = launch_gemm(g, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
+int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_s, int64_t R_a, int64_t R_b,
+               int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream)
+{
+    return mxfp4_gemm_fmt(a_q, a_s, MXFP4_FMT_E2M1, b_q, b_s, MXFP4_FMT_E2M1, R_a, R_b, C, out, ld_out, out_dtype,
+                          accumulate, hip_stream);
 }
 
 // One dense tensor of a linear layer, quantised in the layer's geometry: the row-wise output (q_last, s_last),

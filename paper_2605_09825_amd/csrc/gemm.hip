@@ -25,14 +25,6 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ v4f mfma_fp4(v4i first, v4i second, v4f acc, int scale_first, int scale_second)
-{
-    v8i a = {first.x, first.y, first.z, first.w, 0, 0, 0, 0};
-    v8i b = {second.x, second.y, second.z, second.w, 0, 0, 0, 0};
-    // cbsz = blgp = 4: both operands E2M1; scale byte 0 of each scale register
-    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc, 4, 4, 0, scale_first, 0, scale_second);
-}
-
 __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 {
     // round to nearest even on the upper 16 bits; NaN keeps a quiet NaN (branch-free)
@@ -56,7 +48,27 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 // 256 threads = 2x2 waves, each wave a 32x32 output tile (2x2 instruction tiles); operands
 // come straight from global memory.  Rows beyond the matrix are clamped (their results
 // are dropped), K blocks beyond C/32 are fed as zeros.
-template <bool OUT_FP32, bool ACC>
+// AF, BF: element format of each operand, 0 = E2M1 (16 bytes per 32-element block), 1 = E4M3 (32 bytes);
+// the instruction's format selectors are 4 for E2M1 and 0 for E4M3.
+// One lane's operand registers for the 128 K-elements starting at block k (a multiple of 4), lane group kb.
+// E2M1: the lane holds block k + kb, 32 consecutive elements in 16 bytes.  E4M3 (probed on the hardware): the
+// lane holds elements 16*kb .. +15 and 64 + 16*kb .. +15 of the 128, 16 bytes each, while its scale register
+// still belongs to block k + kb.  Blocks at or beyond nkb read as zeros.
+template <int F>
+__device__ __forceinline__ v8i load_operand(const uint8_t *q, int64_t row, int64_t C, int64_t nkb, int64_t k, int kb)
+{
+    const v4i zero = {0, 0, 0, 0};
+    if (F == 0) {
+        const v4i t = (k + kb < nkb) ? *reinterpret_cast<const v4i *>(q + row * (C >> 1) + (k + kb) * 16) : zero;
+        return (v8i){t.x, t.y, t.z, t.w, 0, 0, 0, 0};
+    }
+    const uint8_t *p = q + row * C + k * 32;
+    const v4i t0 = (k + (kb >> 1) < nkb) ? *reinterpret_cast<const v4i *>(p + 16 * kb) : zero;
+    const v4i t1 = (k + 2 + (kb >> 1) < nkb) ? *reinterpret_cast<const v4i *>(p + 64 + 16 * kb) : zero;
+    return (v8i){t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+}
+
+template <bool OUT_FP32, bool ACC, int AF, int BF>
 __global__ __launch_bounds__(256) void gemm_any_kernel(const uint8_t *__restrict__ aq, const uint8_t *__restrict__ as,
                                                        const uint8_t *__restrict__ bq, const uint8_t *__restrict__ bs,
                                                        int64_t Ra, int64_t Rb, int64_t C, void *__restrict__ out,
@@ -66,7 +78,7 @@ __global__ __launch_bounds__(256) void gemm_any_kernel(const uint8_t *__restrict
     const int l16 = lane & 15, kb = lane >> 4;
     const int64_t row0 = (int64_t)blockIdx.x * 64 + (wave >> 1) * 32;
     const int64_t col0 = (int64_t)blockIdx.y * 64 + (wave & 1) * 32;
-    const int64_t nkb = C >> 5, rowbytes = C >> 1;
+    const int64_t nkb = C >> 5;
 
     int64_t ar[2], br[2];
 #pragma unroll
@@ -82,27 +94,22 @@ __global__ __launch_bounds__(256) void gemm_any_kernel(const uint8_t *__restrict
         for (int j = 0; j < 2; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
 
     for (int64_t k = 0; k < nkb; k += 4) {
-        const int64_t kk = k + kb;
-        const bool kv = kk < nkb;
-        v4i a[2], b[2];
+        const bool kv = k + kb < nkb;
+        v8i a[2], b[2];
         int sa[2], sb[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            a[t] = (v4i){0, 0, 0, 0};
-            b[t] = (v4i){0, 0, 0, 0};
-            sa[t] = 127;
-            sb[t] = 127;
-            if (kv) {
-                a[t] = *reinterpret_cast<const v4i *>(aq + ar[t] * rowbytes + kk * 16);
-                b[t] = *reinterpret_cast<const v4i *>(bq + br[t] * rowbytes + kk * 16);
-                sa[t] = as[ar[t] * nkb + kk];
-                sb[t] = bs[br[t] * nkb + kk];
-            }
+            a[t] = load_operand<AF>(aq, ar[t], C, nkb, k, kb);
+            b[t] = load_operand<BF>(bq, br[t], C, nkb, k, kb);
+            sa[t] = kv ? as[ar[t] * nkb + k + kb] : 127;
+            sb[t] = kv ? bs[br[t] * nkb + k + kb] : 127;
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) acc[i][j] = mfma_fp4(b[j], a[i], acc[i][j], sb[j], sa[i]);
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[j], a[i], acc[i][j], BF ? 0 : 4,
+                                                                             AF ? 0 : 4, 0, sb[j], 0, sa[i]);
     }
 
 #pragma unroll
@@ -554,7 +561,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p
 // fetched 32 per row, 16-byte aligned), and 16-byte aligned rows everywhere
 static bool tile_eligible(const GemmArgs &g)
 {
-    return g.C >= 1024 && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.C % 512) == 0 && (g.ld % 8) == 0 &&
+    return g.a_fmt == 0 && g.b_fmt == 0 && g.C >= 1024 && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.C % 512) == 0 && (g.ld % 8) == 0 &&
            (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 && (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 &&
            (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) && g.C < (int64_t(1) << 31);
 }
@@ -564,21 +571,28 @@ static TileGemm tile_args(const GemmArgs &g)
     return TileGemm{g.aq, g.as, g.bq, g.bs, g.C, g.out, g.ld, (int)(g.Ra / TILE), (int)(g.Rb / TILE)};
 }
 
-static hipError_t launch_any(const GemmArgs &g, hipStream_t st)
+template <int AF, int BF>
+static hipError_t launch_any_f(const GemmArgs &g, hipStream_t st)
 {
     dim3 grid((unsigned)((g.Ra + 63) / 64), (unsigned)((g.Rb + 63) / 64));
     if (g.out_fp32) {
         if (g.accumulate)
-            hipLaunchKernelGGL((gemm_any_kernel<true, true>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs, g.Ra,
-                               g.Rb, g.C, g.out, g.ld);
+            hipLaunchKernelGGL((gemm_any_kernel<true, true, AF, BF>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs,
+                               g.Ra, g.Rb, g.C, g.out, g.ld);
         else
-            hipLaunchKernelGGL((gemm_any_kernel<true, false>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs, g.Ra,
-                               g.Rb, g.C, g.out, g.ld);
+            hipLaunchKernelGGL((gemm_any_kernel<true, false, AF, BF>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs,
+                               g.Ra, g.Rb, g.C, g.out, g.ld);
     } else {
-        hipLaunchKernelGGL((gemm_any_kernel<false, false>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs, g.Ra,
-                           g.Rb, g.C, g.out, g.ld);
+        hipLaunchKernelGGL((gemm_any_kernel<false, false, AF, BF>), grid, dim3(256), 0, st, g.aq, g.as, g.bq, g.bs,
+                           g.Ra, g.Rb, g.C, g.out, g.ld);
     }
     return hipGetLastError();
+}
+
+static hipError_t launch_any(const GemmArgs &g, hipStream_t st)
+{
+    if (g.a_fmt == 0) return g.b_fmt == 0 ? launch_any_f<0, 0>(g, st) : launch_any_f<0, 1>(g, st);
+    return g.b_fmt == 0 ? launch_any_f<1, 0>(g, st) : launch_any_f<1, 1>(g, st);
 }
 
 static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
@@ -602,10 +616,10 @@ static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
 static GemmArgs sub_block(const GemmArgs &g, int64_t r0, int64_t n, int64_t c0, int64_t m)
 {
     GemmArgs h = g;
-    const int64_t rowbytes = g.C / 2, nkb = g.C / 32;
-    h.aq = g.aq + r0 * rowbytes;
+    const int64_t nkb = g.C / 32;
+    h.aq = g.aq + r0 * (g.a_fmt ? g.C : g.C / 2);
     h.as = g.as + r0 * nkb;
-    h.bq = g.bq + c0 * rowbytes;
+    h.bq = g.bq + c0 * (g.b_fmt ? g.C : g.C / 2);
     h.bs = g.bs + c0 * nkb;
     h.Ra = n;
     h.Rb = m;

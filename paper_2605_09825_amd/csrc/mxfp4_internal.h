@@ -28,12 +28,17 @@ hipError_t launch_quantize_dual(const QuantArgs &a, const QuantArgs *b, hipStrea
 // may be null
 hipError_t launch_quantize_2d(const QuantArgs &a, const QuantArgs *b, hipStream_t st);
 
+// MXFP8 (E4M3) output, round to nearest even: q[R][C] one byte per element, s[R][C/32]; cols_axis selects the
+// column-wise (32x1, transposed output) layout
+hipError_t launch_quantize_fp8(const QuantArgs &a, bool cols_axis, hipStream_t st);
+
 struct GemmArgs {
     const uint8_t *aq, *as, *bq, *bs;
     int64_t Ra, Rb, C;
     void *out;
     int64_t ld;
     int out_fp32, accumulate;
+    int a_fmt = 0, b_fmt = 0;  // element format of each operand: 0 = E2M1 (q[R][C/2]), 1 = E4M3 (q[R][C])
 };
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);

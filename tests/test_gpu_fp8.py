@@ -1,0 +1,148 @@
+"""GPU parity of the MXFP8 (E4M3) pieces used by the stages of the stage-wise recipe that stay in 8 bits
+(Table 1, "MXFP4 GEMMs (others FP8)"): the quantiser must match the oracle byte for byte.  The GEMM is compared
+with the oracle's exact fp64 sum under the tolerance the matrix unit's arithmetic allows: with an E4M3 operand
+the unit adds the products of 8 consecutive K-elements after aligning them to the largest of the 8 and dropping
+what lies below 2^-13 of it (probed), i.e. up to 7 * 2^-13 of a group's sum |a||b| is lost; when the products of
+every group span less than 2^13 nothing is lost and the MXFP4 bound 1e-5 * sum|a||b| holds."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_09825_amd as mx
+from paper_2605_09825_amd import synth
+from gpu_util import first_mismatch
+from test_gpu_gemm import assert_close, gpu, sample_positions
+
+pytestmark = pytest.mark.gpu
+FP8_RTOL = 7 * 2.0 ** -13 + 1e-5
+
+HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16]
+
+
+def check_q(t_cpu, axis, had, seed=0, x_gpu=None):
+    x = t_cpu.to("cuda:0") if x_gpu is None else x_gpu
+    q, s = mx.mxfp4_quantize_fp8(x, axis, had, seed)
+    torch.cuda.synchronize()
+    qo, so = oracle.quantize_fp8(synth.as_u16(t_cpu.contiguous()), axis, had, seed)
+    assert np.array_equal(s.cpu().numpy(), so), "scales: " + first_mismatch(s.cpu().numpy(), so)
+    assert np.array_equal(q.cpu().numpy(), qo), "codes: " + first_mismatch(q.cpu().numpy(), qo)
+
+
+@pytest.mark.parametrize("had", HADS)
+@pytest.mark.parametrize("shape", [(256, 512), (37, 96), (1, 32), (300, 4096)])
+def test_rows(shape, had):
+    check_q(synth.student_t3(shape[0], shape[1], 1.0, 3, synth.STREAM_X), mx.AXIS_LAST, had, seed=11)
+
+
+@pytest.mark.parametrize("had", HADS)
+@pytest.mark.parametrize("shape", [(256, 128), (96, 74), (32, 2), (288, 130), (1056, 258), (512, 1024)])
+def test_cols(shape, had):
+    check_q(synth.student_t3(shape[0], shape[1], 1.0, 4, synth.STREAM_DY), mx.AXIS_FIRST, had, seed=12)
+
+
+@pytest.mark.parametrize("axis", [mx.AXIS_LAST, mx.AXIS_FIRST])
+@pytest.mark.parametrize("had", HADS)
+def test_every_bf16_bit_pattern_and_distributions(axis, had):
+    bits = np.arange(65536, dtype=np.uint16).reshape(256, 256)  # includes zeros, subnormals, infinities, NaNs
+    check_q(synth.from_bits(bits), axis, had)
+    finite = bits.reshape(-1)[(bits.reshape(-1) & 0x7F80) != 0x7F80]
+    mixed = np.random.default_rng(0).permutation(finite)[: 96 * 512].reshape(96, 512)
+    check_q(synth.from_bits(mixed), axis, had)
+    check_q(synth.normal_with_outlier_channels(512, 1024, 6, synth.STREAM_X, fraction=0.004), axis, had)
+    check_q(synth.normal(256, 512, 1e-30, 6, synth.STREAM_W), axis, had)
+    check_q(synth.normal(256, 512, 1e30, 6, synth.STREAM_W), axis, had)
+    base = synth.normal(320, 640, 1.0, 5, synth.STREAM_X)
+    check_q(base[32:288, 64:576], axis, had, x_gpu=base.to("cuda:0")[32:288, 64:576])
+
+
+def rand_fp8(rng, R, C):
+    q = rng.integers(0, 127, size=(R, C), dtype=np.uint8) | (rng.integers(0, 2, size=(R, C), dtype=np.uint8) << 7)
+    return q, rng.integers(115, 135, size=(R, C // 32), dtype=np.uint8)
+
+
+def rand_fp4(rng, R, C):
+    return rng.integers(0, 256, size=(R, C // 2), dtype=np.uint8), rng.integers(115, 135, size=(R, C // 32), dtype=np.uint8)
+
+
+@pytest.mark.parametrize("fmts", [(1, 1), (1, 0), (0, 1)])
+@pytest.mark.parametrize("shape", [(64, 64, 128), (37, 53, 96), (1, 1, 32), (256, 512, 512), (130, 70, 1024),
+                                   (512, 768, 1536), (300, 520, 1024)])
+def test_gemm_random_codes(shape, fmts):
+    Ra, Rb, C = shape
+    rng = np.random.default_rng(Ra * 7 + Rb * 3 + C + 100 * fmts[0] + 10 * fmts[1])
+    aq, as_ = (rand_fp8 if fmts[0] else rand_fp4)(rng, Ra, C)
+    bq, bs = (rand_fp8 if fmts[1] else rand_fp4)(rng, Rb, C)
+    want, absum = oracle.gemm_fmt(aq, as_, fmts[0], bq, bs, fmts[1])
+    got = mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out_dtype=mx.OUT_FP32, a_format=fmts[0], b_format=fmts[1])
+    torch.cuda.synchronize()
+    assert np.all(np.abs(got.cpu().numpy() - want) <= FP8_RTOL * absum)
+    b16 = mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out_dtype=mx.OUT_BF16, a_format=fmts[0], b_format=fmts[1])
+    acc = got.clone()
+    mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out=acc, out_dtype=mx.OUT_FP32, accumulate=True,
+                  a_format=fmts[0], b_format=fmts[1])
+    torch.cuda.synchronize()
+    assert torch.equal(b16.cpu(), got.cpu().to(torch.bfloat16)) and torch.equal(acc, got + got)
+
+
+@pytest.mark.parametrize("fmts", [(1, 1), (1, 0), (0, 1)])
+@pytest.mark.parametrize("shape", [(64, 64, 128), (37, 53, 96), (256, 512, 512), (300, 520, 1024)])
+def test_gemm_narrow_exponent_range_meets_the_mxfp4_bound(shape, fmts):
+    # E4M3 exponent fields 5..9 (magnitudes 0.25 .. 7.5), any E2M1 code but zero excluded from neither: the
+    # products inside a group of 8 then span at most 2^5 * 15 * 12 < 2^13, so no bit is dropped
+    Ra, Rb, C = shape
+    rng = np.random.default_rng(Ra + Rb + C + 7 * fmts[0] + fmts[1])
+
+    def narrow_fp8(R):
+        q = (rng.integers(5, 10, size=(R, C), dtype=np.uint8) << 3) | rng.integers(0, 8, size=(R, C), dtype=np.uint8)
+        q |= rng.integers(0, 2, size=(R, C), dtype=np.uint8) << 7
+        return q.astype(np.uint8), np.full((R, C // 32), 127, dtype=np.uint8) + rng.integers(0, 2, size=(R, C // 32), dtype=np.uint8) * 0
+
+    def fp4_nonzero(R):
+        codes = rng.integers(1, 8, size=(R, C), dtype=np.uint8) | (rng.integers(0, 2, size=(R, C), dtype=np.uint8) << 3)
+        return (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8), np.full((R, C // 32), 127, dtype=np.uint8)
+
+    aq, as_ = (narrow_fp8 if fmts[0] else fp4_nonzero)(Ra)
+    bq, bs = (narrow_fp8 if fmts[1] else fp4_nonzero)(Rb)
+    # per-row scales that differ between rows (not inside a row: a group of 8 lies inside one block anyway,
+    # but keep the spread argument simple)
+    as_ = (as_ + rng.integers(-6, 7, size=(Ra, 1))).astype(np.uint8)
+    bs = (bs + rng.integers(-6, 7, size=(Rb, 1))).astype(np.uint8)
+    want, absum = oracle.gemm_fmt(aq, as_, fmts[0], bq, bs, fmts[1])
+    got = mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out_dtype=mx.OUT_FP32, a_format=fmts[0], b_format=fmts[1])
+    torch.cuda.synchronize()
+    assert_close(got.cpu().numpy(), want, absum)
+
+
+def test_fp8_linear_stage_on_real_operands():
+    # Fprop of a small layer entirely in MXFP8, deterministic rotation: quantise both operands, multiply
+    M, K, N = 256, 512, 384
+    x = synth.normal(M, K, 1.0, 1, synth.STREAM_X)
+    w = synth.normal(N, K, 0.02, 1, synth.STREAM_W)
+    xq, xs = mx.mxfp4_quantize_fp8(x.to("cuda:0"), mx.AXIS_LAST, mx.HAD_DET)
+    wq, ws = mx.mxfp4_quantize_fp8(w.to("cuda:0"), mx.AXIS_LAST, mx.HAD_DET)
+    y = mx.mxfp4_gemm(xq, xs, wq, ws, out_dtype=mx.OUT_FP32, a_format=mx.FMT_E4M3, b_format=mx.FMT_E4M3)
+    torch.cuda.synchronize()
+    xo = oracle.quantize_fp8(synth.as_u16(x), oracle.AXIS_LAST, oracle.HAD_DET)
+    wo = oracle.quantize_fp8(synth.as_u16(w), oracle.AXIS_LAST, oracle.HAD_DET)
+    want, absum = oracle.gemm_fmt(xo[0], xo[1], 1, wo[0], wo[1], 1)
+    assert np.all(np.abs(y.cpu().numpy() - want) <= FP8_RTOL * absum)
+    # and it is much closer to the real product than the MXFP4 version of the same layer
+    ref = x.to(torch.float64) @ w.to(torch.float64).T
+    e8 = float(torch.linalg.norm(y.cpu().to(torch.float64) - ref) / torch.linalg.norm(ref))
+    y4, _ = mx.mxfp4_linear_fwd(x.to("cuda:0"), w.to("cuda:0"), mx.make_cfg(mx.HAD_DET, y_dtype=mx.OUT_FP32))
+    e4 = float(torch.linalg.norm(y4.cpu().to(torch.float64) - ref) / torch.linalg.norm(ref))
+    assert e8 < 0.05 and e8 < e4 / 3, (e8, e4)
+
+
+def test_fp8_argument_errors():
+    x = torch.zeros((64, 48), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_quantize_fp8(x)
+    assert e.value.status == mx.ESHAPE
+    q = torch.zeros((16, 32), dtype=torch.uint8, device="cuda:0")
+    s = torch.zeros((16, 1), dtype=torch.uint8, device="cuda:0")
+    out = torch.zeros((16, 16), dtype=torch.float32, device="cuda:0")
+    rc = mx.lib().mxfp4_gemm_fmt(q.data_ptr(), s.data_ptr(), 5, q.data_ptr(), s.data_ptr(), 1, 16, 16, 32,
+                                 out.data_ptr(), 16, mx.OUT_FP32, 0, None)
+    assert rc == mx.EINVAL

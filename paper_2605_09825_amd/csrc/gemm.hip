@@ -188,7 +188,13 @@ struct TileSrc {
 // The whole tiled GEMM as seen by one workgroup: `wg` of `nwg` workgroups share the problem (the ids are
 // virtual: a launch may run two problems side by side on disjoint sets of CUs).  smem: the workgroup's
 // LDS_BYTES of LDS, lds0 its LDS address.
-template <bool OUT_FP32, bool ACC>
+// FMT: element format of both operands.  0 = E2M1: a stage (128 bytes per row) holds 256 K-elements = 4
+// instruction K-steps, one fragment (16 bytes per lane) each.  1 = E4M3: a stage holds 128 K-elements = 2
+// instruction K-steps of 32 bytes per lane.  The instruction wants, from lane group h, the elements 16h .. +15
+// and 32 + 16h .. +15 of its 64 (probed), which are exactly the two 16-byte fragments the E2M1 path fetches
+// for its K-steps 2j and 2j+1: so data movement, LDS layout and fragment reads are the same for both formats,
+// and only the matrix instructions differ (16 per two phases instead of 16 per phase, taking two fragments).
+template <bool OUT_FP32, bool ACC, int FMT>
 __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, const uint8_t *__restrict__ as,
                                                const uint8_t *__restrict__ bq, const uint8_t *__restrict__ bs,
                                                int64_t C, void *__restrict__ out, int64_t ld, int tiles_m,
@@ -199,8 +205,10 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t rowbytes = C >> 1, nkb = C >> 5;
-    const int nstages = (int)(C / STAGE_K);  // even and >= 4 (the host checks C % 512 == 0, C >= 1024)
+    const int64_t rowbytes = FMT ? C : (C >> 1), nkb = C >> 5;
+    const int nstages = (int)(rowbytes / (STAGE_K / 2));  // even; >= 4 (E2M1) or >= 8 (E4M3): the host checks
+    constexpr int BATCH = FMT ? 8 : 4;   // stages per scale batch (32 scale bytes per row)
+    constexpr int SC_STAGE = FMT ? 4 : 8;  // scale bytes per row and stage
 
     // ---- persistent tile schedule -----------------------------------------------------------
     // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  XCD x owns a
@@ -252,7 +260,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // Scale batch b holds the 32 scale bytes per row of stages first(b) .. first(b)+3, where
     // first(b) = min(4b, nstages-4): the last batch is pulled back so that it never reads past a
     // row's end (batches past the end of K just repeat the last one into the idle buffer).
-    auto batch_first = [&](int b) { return (4 * b < nstages - 4) ? 4 * b : nstages - 4; };
+    auto batch_first = [&](int b) { return (BATCH * b < nstages - BATCH) ? BATCH * b : nstages - BATCH; };
     // instruction j (0..3) of batch b for this wave: j>>1 = operand, j&1 = which 32 of its 64 rows
     // Batch b of a tile lives in scale buffer (b ^ par) & 1; par alternates between tiles so that
     // a tile's first batch never lands in the buffer its predecessor's last batch is still read from.
@@ -260,7 +268,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         const uint8_t *rows = (j >> 1) ? t.bs : t.as;
         const uint32_t dst = lds0 + OFF_SC + ((b ^ par) & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES +
                              (wave * 64 + (j & 1) * 32) * 32;
-        dma16(dst, svoff, rows + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * 8);
+        dma16(dst, svoff, rows + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * SC_STAGE);
     };
 
     // ---- fragment reads: per-lane offsets ---------------------------------------------------
@@ -272,9 +280,10 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     for (int kk = 0; kk < 4; ++kk) foff[kk] = fl0 + (uint32_t)((((kk << 1) | fh) ^ fm) << 4);
     const uint32_t a_frag0 = OFF_A + wm * 16 * 1024, b_frag0 = OFF_B + wn * 16 * 1024;
     const uint32_t sa_frag0 = OFF_SC + (wm * 128 + fr) * 32, sb_frag0 = OFF_SC + SC_OP_BYTES + (wn * 128 + fr) * 32;
-    const uint32_t perm_sel = fh ? 0x07050301u : 0x06040200u;
+    // scale bytes of one stage -> one register whose byte k is the lane's block in instruction K-step k
+    const uint32_t perm_sel = FMT ? (fh ? 0x03010301u : 0x02000200u) : (fh ? 0x07050301u : 0x06040200u);
 
-    v4i fa[2][4], fb[2][4];
+    v4i fa[FMT ? 4 : 2][4], fb[FMT ? 4 : 2][4];
     uint2 sraw[8];
     int sa_cur[4], sb_cur[4];
     // One fragment fetch (f = 0..7: A0,B0,A1,B1,...) of K-step kk of buffer buf into register set `set`.
@@ -287,9 +296,12 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     };
     // The 8 scale bytes of stage s for fragment row f (0..7: A0,B0,A1,B1,...), raw.
     auto read_scale_one = [&](int s, int f, int par) {
-        const int b = s >> 2;
-        const uint8_t *p = smem + ((b ^ par) & 1) * SC_BUF_BYTES + (s - batch_first(b)) * 8 + (f >> 1) * 1024;
-        sraw[f] = *reinterpret_cast<const uint2 *>(p + ((f & 1) ? sb_frag0 : sa_frag0));
+        const int b = s / BATCH;
+        const uint8_t *p = smem + ((b ^ par) & 1) * SC_BUF_BYTES + (s - batch_first(b)) * SC_STAGE + (f >> 1) * 1024;
+        if (FMT)
+            sraw[f] = make_uint2(*reinterpret_cast<const uint32_t *>(p + ((f & 1) ? sb_frag0 : sa_frag0)), 0u);
+        else
+            sraw[f] = *reinterpret_cast<const uint2 *>(p + ((f & 1) ? sb_frag0 : sa_frag0));
     };
     // raw scale bytes -> one register per fragment row whose bytes are K blocks fh, 2+fh, 4+fh, 6+fh
     auto permute_scales = [&]() {
@@ -312,6 +324,25 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         v8i fa8 = {fa[SET][i_].x, fa[SET][i_].y, fa[SET][i_].z, fa[SET][i_].w, 0, 0, 0, 0};                     \
         acc[i_][j_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8, fa8, (FRESH) ? zero16 : acc[i_][j_], \
                                                                       4, 4, KK, sb_cur[j_], KK, sa_cur[i_]);    \
+    }
+    // E4M3: instruction n (0..15) of instruction K-step KS (0/1): fragments 2*KS (low half) and 2*KS+1
+#define MXFP8_MMA(KS, N, FRESH)                                                                                 \
+    {                                                                                                           \
+        constexpr int i_ = (N) >> 2, j_ = (N) & 3;                                                              \
+        v8i fb8 = {fb[2 * (KS)][j_].x, fb[2 * (KS)][j_].y, fb[2 * (KS)][j_].z, fb[2 * (KS)][j_].w,              \
+                   fb[2 * (KS) + 1][j_].x, fb[2 * (KS) + 1][j_].y, fb[2 * (KS) + 1][j_].z, fb[2 * (KS) + 1][j_].w}; \
+        v8i fa8 = {fa[2 * (KS)][i_].x, fa[2 * (KS)][i_].y, fa[2 * (KS)][i_].z, fa[2 * (KS)][i_].w,              \
+                   fa[2 * (KS) + 1][i_].x, fa[2 * (KS) + 1][i_].y, fa[2 * (KS) + 1][i_].z, fa[2 * (KS) + 1][i_].w}; \
+        acc[i_][j_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8, fa8, (FRESH) ? zero16 : acc[i_][j_], \
+                                                                      0, 0, KS, sb_cur[j_], KS, sa_cur[i_]);    \
+    }
+    // phase P (0..3) of a stage, slot N (0..15): E2M1 issues instruction N of K-step P; E4M3 issues, in even
+    // slots, instruction N/2 (+8 in odd phases) of K-step P/2
+#define MXFP4_SLOT_MMA(P, N, FRESH)                                                                             \
+    if (FMT == 0) {                                                                                             \
+        MXFP4_MMA((P) & 1, P, N, FRESH)                                                                         \
+    } else if (((N) & 1) == 0) {                                                                                \
+        MXFP8_MMA((P) >> 1, ((N) >> 1) + 8 * ((P) & 1), FRESH)                                                  \
     }
 #define MXFP4_PIN() __builtin_amdgcn_sched_barrier(0);
 #define MXFP4_16(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)
@@ -337,20 +368,20 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         constexpr int MODE = decltype(mode)::value;
         const int buf = s & 1;
 #define MXFP4_K0(N)                                                                              \
-        if ((N) < 8) read_one(buf, 1, 1, (N));                                                   \
+        if ((N) < 8) read_one(buf, FMT ? 2 : 1, FMT ? 2 : 1, (N));                               \
         if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, 8 + ((N) >> 1));              \
         if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, 8 + ((N) >> 1));      \
-        MXFP4_MMA(0, 0, N, MODE == 3) MXFP4_PIN()
+        MXFP4_SLOT_MMA(0, N, MODE == 3) MXFP4_PIN()
         MXFP4_16(MXFP4_K0)
 #undef MXFP4_K0
 #define MXFP4_K1(N)                                                                              \
-        if ((N) < 8) read_one(buf, 2, 0, (N));                                                   \
-        MXFP4_MMA(1, 1, N, false) MXFP4_PIN()
+        if ((N) < 8) read_one(buf, FMT ? 3 : 2, FMT ? 3 : 0, (N));                               \
+        MXFP4_SLOT_MMA(1, N, FMT && MODE == 3) MXFP4_PIN()
         MXFP4_16(MXFP4_K1)
 #undef MXFP4_K1
 #define MXFP4_K2(N)                                                                              \
-        if ((N) < 8) read_one(buf, 3, 1, (N));                                                   \
-        MXFP4_MMA(0, 2, N, false) MXFP4_PIN()
+        if (!FMT && (N) < 8) read_one(buf, 3, 1, (N));                                           \
+        MXFP4_SLOT_MMA(2, N, false) MXFP4_PIN()
         MXFP4_16(MXFP4_K2)
 #undef MXFP4_K2
         // every wave has fetched its last fragments of this buffer, and this wave's loads of the
@@ -359,13 +390,14 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         __syncthreads();
 #define MXFP4_K3(N)                                                                              \
         if (MODE != 2 && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                                   \
+        if (FMT && MODE != 2 && (N) < 8) read_one(buf ^ 1, 1, 1, (N));                            \
         if (MODE != 2 && (N) >= 8) read_scale_one(s + 1, (N) - 8, par);                           \
         if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, (N) >> 1);                       \
-        if ((MODE == 0 || MODE == 3) && (N) == 14) issue_scales(cur, ((s + 1) >> 2) + 1, (s + 1) & 3, par); \
+        if ((MODE == 0 || MODE == 3) && (N) == 14) issue_scales(cur, (s + 1) / BATCH + 1, (s + 1) & 3, par); \
         if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, (N) >> 1);                \
         if (MODE == 1 && !((N) & 1) && (N) < 8) issue_scales(nxt, 0, (N) >> 1, par_nxt);         \
         if (MODE == 2 && (N) == 1) issue_scales(nxt, 1, 0, par_nxt);                             \
-        MXFP4_MMA(1, 3, N, false) MXFP4_PIN()
+        MXFP4_SLOT_MMA(3, N, false) MXFP4_PIN()
         MXFP4_16(MXFP4_K3)
 #undef MXFP4_K3
         if (MODE != 2) permute_scales();
@@ -384,7 +416,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     for (int j = 0; j < 4; ++j) issue_scales(cur, 0, j, 0);
     issue_scales(cur, 1, 0, 0);
     int par = 0;
-    const int b_last = (nstages - 1) >> 2;
+    const int b_last = (nstages - 1) / BATCH;
 
     for (int lloc = lw; lloc < count_x; lloc += nwg_x) {
         const int par_nxt = (b_last ^ par ^ 1) & 1;
@@ -400,6 +432,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #pragma unroll
         for (int f = 0; f < 8; ++f) {
             read_one(0, 0, 0, f);
+            if (FMT) read_one(0, 1, 1, f);
             read_scale_one(0, f, par);
         }
         permute_scales();
@@ -514,6 +547,8 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // nothing may still be writing this workgroup's LDS when it retires
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #undef MXFP4_MMA
+#undef MXFP8_MMA
+#undef MXFP4_SLOT_MMA
 #undef MXFP4_PIN
 #undef MXFP4_16
 }
@@ -526,12 +561,12 @@ struct TileGemm {
     int tiles_m, tiles_n;
 };
 
-template <bool OUT_FP32, bool ACC>
+template <bool OUT_FP32, bool ACC, int FMT>
 __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const TileGemm p)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
-    gemm_tile_body<OUT_FP32, ACC>(p.aq, p.as, p.bq, p.bs, p.C, p.out, p.ld, p.tiles_m, p.tiles_n, blockIdx.x,
+    gemm_tile_body<OUT_FP32, ACC, FMT>(p.aq, p.as, p.bq, p.bs, p.C, p.out, p.ld, p.tiles_m, p.tiles_n, blockIdx.x,
                                   gridDim.x, smem, lds0);
 }
 
@@ -548,10 +583,10 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const uint32_t xcd = blockIdx.x & 7, lw = blockIdx.x >> 3;
     if (lw < (uint32_t)n0)
-        gemm_tile_body<OUT0, false>(p0.aq, p0.as, p0.bq, p0.bs, p0.C, p0.out, p0.ld, p0.tiles_m, p0.tiles_n,
+        gemm_tile_body<OUT0, false, 0>(p0.aq, p0.as, p0.bq, p0.bs, p0.C, p0.out, p0.ld, p0.tiles_m, p0.tiles_n,
                                     lw * 8 + xcd, (uint32_t)n0 * 8, smem, lds0);
     else
-        gemm_tile_body<OUT1, ACC1>(p1.aq, p1.as, p1.bq, p1.bs, p1.C, p1.out, p1.ld, p1.tiles_m, p1.tiles_n,
+        gemm_tile_body<OUT1, ACC1, 0>(p1.aq, p1.as, p1.bq, p1.bs, p1.C, p1.out, p1.ld, p1.tiles_m, p1.tiles_n,
                                    (lw - n0) * 8 + xcd, (uint32_t)(32 - n0) * 8, smem, lds0);
 }
 
@@ -561,7 +596,9 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p
 // fetched 32 per row, 16-byte aligned), and 16-byte aligned rows everywhere
 static bool tile_eligible(const GemmArgs &g)
 {
-    return g.a_fmt == 0 && g.b_fmt == 0 && g.C >= 1024 && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.C % 512) == 0 && (g.ld % 8) == 0 &&
+    if (g.a_fmt != g.b_fmt) return false;  // mixed formats: any-shape kernel
+    const bool k_ok = g.a_fmt ? (g.C >= 1024 && (g.C % 256) == 0) : (g.C >= 1024 && (g.C % 512) == 0);
+    return k_ok && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.ld % 8) == 0 &&
            (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 && (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 &&
            (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) && g.C < (int64_t(1) << 31);
 }
@@ -595,7 +632,8 @@ static hipError_t launch_any(const GemmArgs &g, hipStream_t st)
     return g.b_fmt == 0 ? launch_any_f<1, 0>(g, st) : launch_any_f<1, 1>(g, st);
 }
 
-static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
+template <int FMT>
+static hipError_t launch_tiled_f(const GemmArgs &g, hipStream_t st)
 {
     const TileGemm p = tile_args(g);
     // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
@@ -603,13 +641,18 @@ static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
     dim3 grid((unsigned)(T < NUM_CUS ? T : NUM_CUS));
     if (g.out_fp32) {
         if (g.accumulate)
-            hipLaunchKernelGGL((gemm_tile_kernel<true, true>), grid, dim3(256), 0, st, p);
+            hipLaunchKernelGGL((gemm_tile_kernel<true, true, FMT>), grid, dim3(256), 0, st, p);
         else
-            hipLaunchKernelGGL((gemm_tile_kernel<true, false>), grid, dim3(256), 0, st, p);
+            hipLaunchKernelGGL((gemm_tile_kernel<true, false, FMT>), grid, dim3(256), 0, st, p);
     } else {
-        hipLaunchKernelGGL((gemm_tile_kernel<false, false>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((gemm_tile_kernel<false, false, FMT>), grid, dim3(256), 0, st, p);
     }
     return hipGetLastError();
+}
+
+static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
+{
+    return g.a_fmt ? launch_tiled_f<1>(g, st) : launch_tiled_f<0>(g, st);
 }
 
 // rows r0.. (n of them) of A and columns c0.. (m of them) of B: the same problem on a sub-block of the output
@@ -655,7 +698,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
 // when both fit the tiled kernel and together fill the chip; otherwise one after the other.
 hipError_t launch_gemm_pair(const GemmArgs &g0, const GemmArgs &g1, hipStream_t st)
 {
-    const bool side_by_side = !g0.accumulate && tile_eligible(g0) && tile_eligible(g1);
+    const bool side_by_side = !g0.accumulate && g0.a_fmt == 0 && g1.a_fmt == 0 && tile_eligible(g0) && tile_eligible(g1);
     if (side_by_side) {
         const TileGemm p0 = tile_args(g0), p1 = tile_args(g1);
         const int64_t t0 = (int64_t)p0.tiles_m * p0.tiles_n, t1 = (int64_t)p1.tiles_m * p1.tiles_n;

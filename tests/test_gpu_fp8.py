@@ -67,7 +67,8 @@ def rand_fp4(rng, R, C):
 
 @pytest.mark.parametrize("fmts", [(1, 1), (1, 0), (0, 1)])
 @pytest.mark.parametrize("shape", [(64, 64, 128), (37, 53, 96), (1, 1, 32), (256, 512, 512), (130, 70, 1024),
-                                   (512, 768, 1536), (300, 520, 1024)])
+                                   (512, 768, 1536), (300, 520, 1024), (256, 256, 1024), (768, 512, 2560),
+                                   (512, 256, 1280)])
 def test_gemm_random_codes(shape, fmts):
     Ra, Rb, C = shape
     rng = np.random.default_rng(Ra * 7 + Rb * 3 + C + 100 * fmts[0] + 10 * fmts[1])
@@ -86,7 +87,9 @@ def test_gemm_random_codes(shape, fmts):
 
 
 @pytest.mark.parametrize("fmts", [(1, 1), (1, 0), (0, 1)])
-@pytest.mark.parametrize("shape", [(64, 64, 128), (37, 53, 96), (256, 512, 512), (300, 520, 1024)])
+@pytest.mark.parametrize("shape", [(64, 64, 128), (37, 53, 96), (256, 512, 512), (300, 520, 1024),
+                                   (256, 256, 1024), (512, 768, 1536), (768, 512, 2560), (512, 256, 1280),
+                                   (1280, 1024, 4096)])
 def test_gemm_narrow_exponent_range_meets_the_mxfp4_bound(shape, fmts):
     # E4M3 exponent fields 5..9 (magnitudes 0.25 .. 7.5), any E2M1 code but zero excluded from neither: the
     # products inside a group of 8 then span at most 2^5 * 15 * 12 < 2^13, so no bit is dropped
@@ -112,6 +115,33 @@ def test_gemm_narrow_exponent_range_meets_the_mxfp4_bound(shape, fmts):
     got = mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out_dtype=mx.OUT_FP32, a_format=fmts[0], b_format=fmts[1])
     torch.cuda.synchronize()
     assert_close(got.cpu().numpy(), want, absum)
+
+
+@pytest.mark.parametrize("C", [1024, 2304])
+def test_fp8_many_tiles_per_workgroup_sampled(C):
+    # 17 x 17 = 289 tiles of 256 x 256: more than one tile per CU, so tiles hand over inside a workgroup;
+    # narrow exponent range, so the MXFP4 bound applies (a wrong hand-over would show as a gross error)
+    Ra = Rb = 256 * 17
+    rng = np.random.default_rng(C)
+
+    def narrow(R):
+        q = (rng.integers(5, 10, size=(R, C), dtype=np.uint8) << 3) | rng.integers(0, 8, size=(R, C), dtype=np.uint8)
+        q |= rng.integers(0, 2, size=(R, C), dtype=np.uint8) << 7
+        srow = (127 + rng.integers(-6, 7, size=(R, 1))).astype(np.uint8)  # one scale per row (see above)
+        return q.astype(np.uint8), np.ascontiguousarray(np.broadcast_to(srow, (R, C // 32)))
+
+    aq, as_ = narrow(Ra)
+    bq, bs = narrow(Rb)
+    for dt in (mx.OUT_FP32, mx.OUT_BF16):
+        out = mx.mxfp4_gemm(gpu(aq), gpu(as_), gpu(bq), gpu(bs), out_dtype=dt, a_format=1, b_format=1)
+        torch.cuda.synchronize()
+        ii, jj = sample_positions(rng, Ra, Rb, n_rows=3, n_cols=3, n_tiles=64)
+        want, absum = oracle.gemm_at_fmt(aq, as_, 1, bq, bs, 1, ii, jj)
+        got = out.float().cpu().numpy()[ii, jj]
+        if dt == mx.OUT_FP32:
+            assert_close(got, want, absum)
+        else:
+            assert (np.abs(got - want) <= 1e-5 * absum + 2.0 ** -8 * np.abs(want)).all()
 
 
 def test_fp8_linear_stage_on_real_operands():

@@ -92,7 +92,9 @@ typedef struct {
     int32_t dw_dtype;      /* mxfp4_out for dW                                                  */
     int32_t dw_accumulate; /* 1: dW += (fp32 only; gradient accumulation), 0: dW =             */
     int32_t geometry;      /* mxfp4_geometry of every quantisation of the layer (App. D)        */
-    int32_t reserved;      /* must be 0                                                         */
+    int32_t fprop_format;  /* mxfp4_format of both operands of Fprop: the stage-wise recipe of Table 1  */
+    int32_t dgrad_format;  /*   ("MXFP4 GEMMs (others FP8)") sets a stage to MXFP4_FMT_E4M3 to keep it  */
+    int32_t wgrad_format;  /*   in 8 bits: MXFP8, no rotation, round to nearest, 1D blocks only         */
 } mxfp4_linear_cfg;
 
 /*
@@ -208,7 +210,7 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
  * X^T (for Wgrad) in `saved`; mxfp4_linear_bwd_saved then needs neither x nor w: it
  * quantises dY both ways in one pass and runs Dgrad and Wgrad against `saved`.  Outputs are
  * bit-identical to mxfp4_linear_fwd / mxfp4_linear_bwd with the same cfg.
- *   saved: device buffer of at least mxfp4_linear_saved_bytes(M,N,K) bytes, 256-byte aligned,
+ *   saved: device buffer of at least mxfp4_linear_saved_bytes(M,N,K,cfg) bytes, 256-byte aligned,
  *          owned by the caller, kept untouched between the two calls; offsets of q and s of
  *          W^T (rows K, C=N) and X^T (rows K, C=M) from mxfp4_linear_saved_layout.
  *   M % 32 == 0, N % 32 == 0, K % 32 == 0, all >= 1 (else MXFP4_ESHAPE).
@@ -221,9 +223,9 @@ int mxfp4_linear_fwd_save(const void *x, const void *w, void *y, int64_t M, int6
 int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes, void *dx, void *dw, int64_t M,
                            int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, void *workspace,
                            size_t workspace_bytes, void *hip_stream);
-size_t mxfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K);
-/* offsets[4]: q, s of W^T then q, s of X^T inside `saved`.  Host-only. */
-int mxfp4_linear_saved_layout(int64_t M, int64_t N, int64_t K, size_t offsets[4]);
+size_t mxfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg);
+/* offsets[4]: q, s of W^T then q, s of X^T inside `saved` (cfg: the stage formats; NULL = all MXFP4).  Host-only. */
+int mxfp4_linear_saved_layout(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, size_t offsets[4]);
 
 /* Bytes of workspace the fused calls need (bwd = 0: forward, 1: backward).  Host-only. */
 size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd);
@@ -233,9 +235,11 @@ size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4
  * leave behind (for byte-parity tests).  offsets[8] receives, in order, q and s of:
  *   bwd = 0: X (rows M, C=K), W (rows N, C=K); entries 4..7 are 0
  *   bwd = 1: dY (rows M, C=N), W^T (rows K, C=N), dY^T (rows N, C=M), X^T (rows K, C=M)
- * Host-only.  Returns MXFP4_OK or MXFP4_EINVAL.
+ * The code array of an operand of an MXFP8 stage holds one byte per element (cfg: the stage formats;
+ * NULL = all MXFP4).  Host-only.  Returns MXFP4_OK or MXFP4_EINVAL.
  */
-int mxfp4_linear_workspace_layout(int64_t M, int64_t N, int64_t K, int bwd, size_t offsets[8]);
+int mxfp4_linear_workspace_layout(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd,
+                                  size_t offsets[8]);
 
 /* Human-readable name of a status code; pointer to static storage, never NULL.  Host-only. */
 const char *mxfp4_status_string(int status);

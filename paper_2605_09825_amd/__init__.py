@@ -34,7 +34,8 @@ class LinearCfg(ctypes.Structure):
     """mxfp4_linear_cfg"""
     _fields_ = [("hadamard", ctypes.c_int32), ("rounding", ctypes.c_int32), ("seed", ctypes.c_uint64),
                 ("y_dtype", ctypes.c_int32), ("dx_dtype", ctypes.c_int32), ("dw_dtype", ctypes.c_int32),
-                ("dw_accumulate", ctypes.c_int32), ("geometry", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("dw_accumulate", ctypes.c_int32), ("geometry", ctypes.c_int32), ("fprop_format", ctypes.c_int32),
+                ("dgrad_format", ctypes.c_int32), ("wgrad_format", ctypes.c_int32)]
 
 
 class Mxfp4Error(RuntimeError):
@@ -70,9 +71,9 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_linear_bwd_saved.restype = ci
         L.mxfp4_linear_bwd_saved.argtypes = [vp, vp, sz, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
         L.mxfp4_linear_saved_bytes.restype = sz
-        L.mxfp4_linear_saved_bytes.argtypes = [i64, i64, i64]
+        L.mxfp4_linear_saved_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(LinearCfg)]
         L.mxfp4_linear_saved_layout.restype = ci
-        L.mxfp4_linear_saved_layout.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+        L.mxfp4_linear_saved_layout.argtypes = [i64, i64, i64, ctypes.POINTER(LinearCfg), ctypes.POINTER(sz)]
         L.mxfp4_gemm.restype = ci
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
         L.mxfp4_linear_fwd.restype = ci
@@ -82,7 +83,7 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_linear_workspace_bytes.restype = sz
         L.mxfp4_linear_workspace_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(LinearCfg), ci]
         L.mxfp4_linear_workspace_layout.restype = ci
-        L.mxfp4_linear_workspace_layout.argtypes = [i64, i64, i64, ci, ctypes.POINTER(sz)]
+        L.mxfp4_linear_workspace_layout.argtypes = [i64, i64, i64, ctypes.POINTER(LinearCfg), ci, ctypes.POINTER(sz)]
         L.mxfp4_status_string.restype = ctypes.c_char_p
         L.mxfp4_status_string.argtypes = [ci]
         _lib = L
@@ -210,17 +211,23 @@ def mxfp4_linear_workspace_bytes(M: int, N: int, K: int, cfg: LinearCfg, bwd: bo
     return int(lib().mxfp4_linear_workspace_bytes(M, N, K, ctypes.byref(cfg), int(bwd)))
 
 
-def mxfp4_linear_workspace_layout(M: int, N: int, K: int, bwd: bool):
+def _cfg_ref(cfg):
+    return None if cfg is None else ctypes.byref(cfg)
+
+
+def mxfp4_linear_workspace_layout(M: int, N: int, K: int, bwd: bool, cfg: Optional[LinearCfg] = None):
     arr = (ctypes.c_size_t * 8)()
-    _check("mxfp4_linear_workspace_layout", lib().mxfp4_linear_workspace_layout(M, N, K, int(bwd), arr))
+    _check("mxfp4_linear_workspace_layout",
+           lib().mxfp4_linear_workspace_layout(M, N, K, _cfg_ref(cfg), int(bwd), arr))
     return [int(v) for v in arr]
 
 
 def make_cfg(hadamard: int = HAD_NONE, rounding: int = RNE, seed: int = 0, y_dtype: int = OUT_BF16,
              dx_dtype: int = OUT_BF16, dw_dtype: int = OUT_FP32, dw_accumulate: bool = False,
-             geometry: int = GEOM_1D) -> LinearCfg:
+             geometry: int = GEOM_1D, fprop_format: int = FMT_E2M1, dgrad_format: int = FMT_E2M1,
+             wgrad_format: int = FMT_E2M1) -> LinearCfg:
     return LinearCfg(hadamard, rounding, seed & (2**64 - 1), y_dtype, dx_dtype, dw_dtype, int(dw_accumulate),
-                     geometry, 0)
+                     geometry, fprop_format, dgrad_format, wgrad_format)
 
 
 def mxfp4_linear_fwd(x, w, cfg: LinearCfg, y=None, workspace=None, stream=None):
@@ -259,13 +266,13 @@ def mxfp4_linear_bwd(dy, x, w, cfg: LinearCfg, dx=None, dw=None, need_dx: bool =
     return dx, dw, workspace
 
 
-def mxfp4_linear_saved_bytes(M: int, N: int, K: int) -> int:
-    return int(lib().mxfp4_linear_saved_bytes(M, N, K))
+def mxfp4_linear_saved_bytes(M: int, N: int, K: int, cfg: Optional[LinearCfg] = None) -> int:
+    return int(lib().mxfp4_linear_saved_bytes(M, N, K, _cfg_ref(cfg)))
 
 
-def mxfp4_linear_saved_layout(M: int, N: int, K: int):
+def mxfp4_linear_saved_layout(M: int, N: int, K: int, cfg: Optional[LinearCfg] = None):
     arr = (ctypes.c_size_t * 4)()
-    _check("mxfp4_linear_saved_layout", lib().mxfp4_linear_saved_layout(M, N, K, arr))
+    _check("mxfp4_linear_saved_layout", lib().mxfp4_linear_saved_layout(M, N, K, _cfg_ref(cfg), arr))
     return [int(v) for v in arr]
 
 
@@ -279,7 +286,7 @@ def mxfp4_linear_fwd_save(x, w, cfg: LinearCfg, y=None, workspace=None, saved=No
     if workspace is None:
         workspace = torch.empty(mxfp4_linear_workspace_bytes(M, N, K, cfg, False), dtype=torch.uint8, device=x.device)
     if saved is None:
-        saved = torch.empty(mxfp4_linear_saved_bytes(M, N, K), dtype=torch.uint8, device=x.device)
+        saved = torch.empty(mxfp4_linear_saved_bytes(M, N, K, cfg), dtype=torch.uint8, device=x.device)
     if y is None:
         y = torch.empty((M, N), dtype=_out_dtype(cfg.y_dtype), device=x.device)
     _check("mxfp4_linear_fwd_save", lib().mxfp4_linear_fwd_save(

@@ -69,16 +69,28 @@ int check_gemm(const void *aq, const void *as, const void *bq, const void *bs, i
     return -1;
 }
 
+// element format of each stage's operands (null cfg: all MXFP4)
+struct StageFormats {
+    int fprop, dgrad, wgrad;
+};
+StageFormats stage_formats(const mxfp4_linear_cfg *cfg)
+{
+    if (!cfg) return StageFormats{MXFP4_FMT_E2M1, MXFP4_FMT_E2M1, MXFP4_FMT_E2M1};
+    return StageFormats{cfg->fprop_format, cfg->dgrad_format, cfg->wgrad_format};
+}
+// bytes of the code array of an operand with R rows and contraction length C
+size_t q_bytes(int64_t R, int64_t C, int fmt) { return (size_t)R * (size_t)(fmt == MXFP4_FMT_E4M3 ? C : C / 2); }
+
 struct FwdLayout {
     size_t xq, xs, wq, ws, total;
 };
-FwdLayout fwd_layout(int64_t M, int64_t N, int64_t K)
+FwdLayout fwd_layout(int64_t M, int64_t N, int64_t K, const StageFormats &f)
 {
     FwdLayout L;
     size_t o = 0;
-    L.xq = o; o = round_up(o + (size_t)M * (K / 2), 256);
+    L.xq = o; o = round_up(o + q_bytes(M, K, f.fprop), 256);
     L.xs = o; o = round_up(o + (size_t)M * (K / 32), 256);
-    L.wq = o; o = round_up(o + (size_t)N * (K / 2), 256);
+    L.wq = o; o = round_up(o + q_bytes(N, K, f.fprop), 256);
     L.ws = o; o = round_up(o + (size_t)N * (K / 32), 256);
     L.total = o;
     return L;
@@ -87,17 +99,17 @@ FwdLayout fwd_layout(int64_t M, int64_t N, int64_t K)
 struct BwdLayout {
     size_t gq, gs, wtq, wts, gtq, gts, xtq, xts, total;
 };
-BwdLayout bwd_layout(int64_t M, int64_t N, int64_t K)
+BwdLayout bwd_layout(int64_t M, int64_t N, int64_t K, const StageFormats &f)
 {
     BwdLayout L;
     size_t o = 0;
-    L.gq = o;  o = round_up(o + (size_t)M * (N / 2), 256);
+    L.gq = o;  o = round_up(o + q_bytes(M, N, f.dgrad), 256);
     L.gs = o;  o = round_up(o + (size_t)M * (N / 32), 256);
-    L.wtq = o; o = round_up(o + (size_t)K * (N / 2), 256);
+    L.wtq = o; o = round_up(o + q_bytes(K, N, f.dgrad), 256);
     L.wts = o; o = round_up(o + (size_t)K * (N / 32), 256);
-    L.gtq = o; o = round_up(o + (size_t)N * (M / 2), 256);
+    L.gtq = o; o = round_up(o + q_bytes(N, M, f.wgrad), 256);
     L.gts = o; o = round_up(o + (size_t)N * (M / 32), 256);
-    L.xtq = o; o = round_up(o + (size_t)K * (M / 2), 256);
+    L.xtq = o; o = round_up(o + q_bytes(K, M, f.wgrad), 256);
     L.xts = o; o = round_up(o + (size_t)K * (M / 32), 256);
     L.total = o;
     return L;
@@ -106,13 +118,13 @@ BwdLayout bwd_layout(int64_t M, int64_t N, int64_t K)
 struct SavedLayout {
     size_t wtq, wts, xtq, xts, total;
 };
-SavedLayout saved_layout(int64_t M, int64_t N, int64_t K)
+SavedLayout saved_layout(int64_t M, int64_t N, int64_t K, const StageFormats &f)
 {
     SavedLayout L;
     size_t o = 0;
-    L.wtq = o; o = round_up(o + (size_t)K * (N / 2), 256);
+    L.wtq = o; o = round_up(o + q_bytes(K, N, f.dgrad), 256);
     L.wts = o; o = round_up(o + (size_t)K * (N / 32), 256);
-    L.xtq = o; o = round_up(o + (size_t)K * (M / 2), 256);
+    L.xtq = o; o = round_up(o + q_bytes(K, M, f.wgrad), 256);
     L.xts = o; o = round_up(o + (size_t)K * (M / 32), 256);
     L.total = o;
     return L;
@@ -129,7 +141,12 @@ int check_cfg(const mxfp4_linear_cfg *cfg)
     if (cfg->dw_accumulate != 0 && cfg->dw_accumulate != 1) return MXFP4_EINVAL;
     if (cfg->dw_accumulate == 1 && cfg->dw_dtype != MXFP4_OUT_FP32) return MXFP4_EINVAL;
     if (cfg->geometry != MXFP4_GEOM_1D && cfg->geometry != MXFP4_GEOM_2D) return MXFP4_EINVAL;
-    if (cfg->reserved != 0) return MXFP4_EINVAL;
+    const int32_t fm[3] = {cfg->fprop_format, cfg->dgrad_format, cfg->wgrad_format};
+    for (int i = 0; i < 3; ++i) {
+        if (fm[i] != MXFP4_FMT_E2M1 && fm[i] != MXFP4_FMT_E4M3) return MXFP4_EINVAL;
+        // the 8-bit stages know only the 1x32 geometry
+        if (fm[i] == MXFP4_FMT_E4M3 && cfg->geometry == MXFP4_GEOM_2D) return MXFP4_ENOTIMPL;
+    }
     return MXFP4_OK;
 }
 
@@ -269,11 +286,28 @@ int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_
                           accumulate, hip_stream);
 }
 
-// One dense tensor of a linear layer, quantised in the layer's geometry: the row-wise output (q_last, s_last),
-// the column-wise one (q_first, s_first), or both from one pass (a null pair = not wanted).
-static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t rows, int64_t cols, uint8_t *q_last,
-                            uint8_t *s_last, uint8_t *q_first, uint8_t *s_first, void *hip_stream)
+// One dense tensor of a linear layer: the row-wise output (q_last, s_last) in format fmt_last, the column-wise
+// one (q_first, s_first) in fmt_first, or both (a null pair = not wanted).  MXFP4 outputs follow the layer's
+// rotation, rounding and geometry, and come from one pass over the tensor when both are MXFP4; an MXFP8 output
+// is unrotated and rounded to nearest (the rotation and the rounding mode are stabilisers of the MXFP4 GEMMs,
+// Table 1).
+static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t rows, int64_t cols, int fmt_last,
+                            uint8_t *q_last, uint8_t *s_last, int fmt_first, uint8_t *q_first, uint8_t *s_first,
+                            void *hip_stream)
 {
+    if (q_last && fmt_last == MXFP4_FMT_E4M3) {
+        int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_LAST, MXFP4_HAD_NONE, cfg->seed, q_last, s_last,
+                                    hip_stream);
+        if (rc != MXFP4_OK) return rc;
+        q_last = s_last = nullptr;
+    }
+    if (q_first && fmt_first == MXFP4_FMT_E4M3) {
+        int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_FIRST, MXFP4_HAD_NONE, cfg->seed, q_first,
+                                    s_first, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+        q_first = s_first = nullptr;
+    }
+    if (!q_last && !q_first) return MXFP4_OK;
     if (cfg->geometry == MXFP4_GEOM_2D)
         return mxfp4_quantize_2d(x, rows, cols, cols, cfg->hadamard, cfg->rounding, cfg->seed, q_last, s_last,
                                  q_first, s_first, hip_stream);
@@ -287,8 +321,8 @@ static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t 
                           s_first, hip_stream);
 }
 
-// Both outputs of two dense tensors (the operands X and W of a forward call that also saves for the backward
-// call) in one launch.
+// Both MXFP4 outputs of two dense tensors (the operands X and W of a forward call that also saves for the
+// backward call) in one launch.
 static int quantize_operand_pair(const mxfp4_linear_cfg *cfg, const void *x0, int64_t rows0, int64_t cols0,
                                  uint8_t *ql0, uint8_t *sl0, uint8_t *qf0, uint8_t *sf0, const void *x1,
                                  int64_t rows1, int64_t cols1, uint8_t *ql1, uint8_t *sl1, uint8_t *qf1,
@@ -338,20 +372,22 @@ static int gemm_pair(const GemmArgs &g0, int dt0, const GemmArgs &g1, int dt1, v
 
 size_t mxfp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd)
 {
-    (void)cfg;
     if (M < 0 || N < 0 || K < 0) return 0;
-    return bwd ? bwd_layout(M, N, K).total : fwd_layout(M, N, K).total;
+    const StageFormats f = stage_formats(cfg);
+    return bwd ? bwd_layout(M, N, K, f).total : fwd_layout(M, N, K, f).total;
 }
 
-int mxfp4_linear_workspace_layout(int64_t M, int64_t N, int64_t K, int bwd, size_t offsets[8])
+int mxfp4_linear_workspace_layout(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, int bwd,
+                                  size_t offsets[8])
 {
     if (!offsets || M < 0 || N < 0 || K < 0) return MXFP4_EINVAL;
+    const StageFormats f = stage_formats(cfg);
     if (bwd) {
-        BwdLayout L = bwd_layout(M, N, K);
+        BwdLayout L = bwd_layout(M, N, K, f);
         const size_t o[8] = {L.gq, L.gs, L.wtq, L.wts, L.gtq, L.gts, L.xtq, L.xts};
         memcpy(offsets, o, sizeof(o));
     } else {
-        FwdLayout L = fwd_layout(M, N, K);
+        FwdLayout L = fwd_layout(M, N, K, f);
         const size_t o[8] = {L.xq, L.xs, L.wq, L.ws, 0, 0, 0, 0};
         memcpy(offsets, o, sizeof(o));
     }
@@ -366,15 +402,17 @@ int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N
     if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0) return MXFP4_ESHAPE;
     if (cfg->geometry == MXFP4_GEOM_2D && ((M % 32) != 0 || (N % 32) != 0)) return MXFP4_ESHAPE;
     if (!x || !w || !y || !workspace) return MXFP4_EINVAL;
-    const FwdLayout L = fwd_layout(M, N, K);
+    const StageFormats F = stage_formats(cfg);
+    const FwdLayout L = fwd_layout(M, N, K, F);
     if (workspace_bytes < L.total) return MXFP4_EWORKSPACE;
     if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    rc = quantize_operand(cfg, x, M, K, ws + L.xq, ws + L.xs, nullptr, nullptr, hip_stream);
+    rc = quantize_operand(cfg, x, M, K, F.fprop, ws + L.xq, ws + L.xs, 0, nullptr, nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    rc = quantize_operand(cfg, w, N, K, ws + L.wq, ws + L.ws, nullptr, nullptr, hip_stream);
+    rc = quantize_operand(cfg, w, N, K, F.fprop, ws + L.wq, ws + L.ws, 0, nullptr, nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    return mxfp4_gemm(ws + L.xq, ws + L.xs, ws + L.wq, ws + L.ws, M, N, K, y, N, cfg->y_dtype, 0, hip_stream);
+    return mxfp4_gemm_fmt(ws + L.xq, ws + L.xs, F.fprop, ws + L.wq, ws + L.ws, F.fprop, M, N, K, y, N, cfg->y_dtype, 0,
+                          hip_stream);
 }
 
 int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw, int64_t M, int64_t N,
@@ -390,7 +428,8 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
     if (!dx && !dw) return MXFP4_OK;
     if (!dy || !workspace) return MXFP4_EINVAL;
     if ((dx && !w) || (dw && !x)) return MXFP4_EINVAL;
-    const BwdLayout L = bwd_layout(M, N, K);
+    const StageFormats F = stage_formats(cfg);
+    const BwdLayout L = bwd_layout(M, N, K, F);
     if (workspace_bytes < L.total) return MXFP4_EWORKSPACE;
     if (!aligned(workspace, 256) || !aligned(dy, 16) || (dx && (!aligned(dx, 16) || !aligned(w, 16))) ||
         (dw && (!aligned(dw, 16) || !aligned(x, 16))))
@@ -398,35 +437,38 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
     if ((N % 8) != 0 || (K % 8) != 0) return MXFP4_EALIGN;  // dense bf16 rows must stay 16-byte aligned
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     // dY is needed row-wise for Dgrad and column-wise for Wgrad: one pass when both are asked
-    rc = quantize_operand(cfg, dy, M, N, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
+    rc = quantize_operand(cfg, dy, M, N, F.dgrad, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr, F.wgrad,
                           dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
     if (dx) {
-        rc = quantize_operand(cfg, w, N, K, nullptr, nullptr, ws + L.wtq, ws + L.wts, hip_stream);
+        rc = quantize_operand(cfg, w, N, K, 0, nullptr, nullptr, F.dgrad, ws + L.wtq, ws + L.wts, hip_stream);
         if (rc != MXFP4_OK) return rc;
     }
     if (dw) {
-        rc = quantize_operand(cfg, x, M, K, nullptr, nullptr, ws + L.xtq, ws + L.xts, hip_stream);
+        rc = quantize_operand(cfg, x, M, K, 0, nullptr, nullptr, F.wgrad, ws + L.xtq, ws + L.xts, hip_stream);
         if (rc != MXFP4_OK) return rc;
     }
-    const GemmArgs gd{ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0};
+    const GemmArgs gd{ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0,
+                      F.dgrad, F.dgrad};
     const GemmArgs gw{ws + L.gtq, ws + L.gts, ws + L.xtq, ws + L.xts, N, K, M, dw, K,
-                      cfg->dw_dtype == MXFP4_OUT_FP32, cfg->dw_accumulate};
+                      cfg->dw_dtype == MXFP4_OUT_FP32, cfg->dw_accumulate, F.wgrad, F.wgrad};
     if (dx && dw) return gemm_pair(gd, cfg->dx_dtype, gw, cfg->dw_dtype, hip_stream);
-    if (dx) return mxfp4_gemm(gd.aq, gd.as, gd.bq, gd.bs, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
-    return mxfp4_gemm(gw.aq, gw.as, gw.bq, gw.bs, N, K, M, dw, K, cfg->dw_dtype, cfg->dw_accumulate, hip_stream);
+    if (dx)
+        return mxfp4_gemm_fmt(gd.aq, gd.as, F.dgrad, gd.bq, gd.bs, F.dgrad, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
+    return mxfp4_gemm_fmt(gw.aq, gw.as, F.wgrad, gw.bq, gw.bs, F.wgrad, N, K, M, dw, K, cfg->dw_dtype,
+                          cfg->dw_accumulate, hip_stream);
 }
 
-size_t mxfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K)
+size_t mxfp4_linear_saved_bytes(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg)
 {
     if (M < 0 || N < 0 || K < 0) return 0;
-    return saved_layout(M, N, K).total;
+    return saved_layout(M, N, K, stage_formats(cfg)).total;
 }
 
-int mxfp4_linear_saved_layout(int64_t M, int64_t N, int64_t K, size_t offsets[4])
+int mxfp4_linear_saved_layout(int64_t M, int64_t N, int64_t K, const mxfp4_linear_cfg *cfg, size_t offsets[4])
 {
     if (!offsets || M < 0 || N < 0 || K < 0) return MXFP4_EINVAL;
-    const SavedLayout L = saved_layout(M, N, K);
+    const SavedLayout L = saved_layout(M, N, K, stage_formats(cfg));
     const size_t o[4] = {L.wtq, L.wts, L.xtq, L.xts};
     memcpy(offsets, o, sizeof(o));
     return MXFP4_OK;
@@ -440,17 +482,26 @@ int mxfp4_linear_fwd_save(const void *x, const void *w, void *y, int64_t M, int6
     if (rc != MXFP4_OK) return rc;
     if (M <= 0 || N <= 0 || K <= 0 || (M % 32) != 0 || (N % 32) != 0 || (K % 32) != 0) return MXFP4_ESHAPE;
     if (!x || !w || !y || !workspace || !saved) return MXFP4_EINVAL;
-    const FwdLayout L = fwd_layout(M, N, K);
-    const SavedLayout S = saved_layout(M, N, K);
+    const StageFormats F = stage_formats(cfg);
+    const FwdLayout L = fwd_layout(M, N, K, F);
+    const SavedLayout S = saved_layout(M, N, K, F);
     if (workspace_bytes < L.total || saved_bytes < S.total) return MXFP4_EWORKSPACE;
     if (!aligned(workspace, 256) || !aligned(saved, 256) || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16))
         return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     uint8_t *sv = static_cast<uint8_t *>(saved);
-    rc = quantize_operand_pair(cfg, x, M, K, ws + L.xq, ws + L.xs, sv + S.xtq, sv + S.xts, w, N, K, ws + L.wq,
-                               ws + L.ws, sv + S.wtq, sv + S.wts, hip_stream);
-    if (rc != MXFP4_OK) return rc;
-    return mxfp4_gemm(ws + L.xq, ws + L.xs, ws + L.wq, ws + L.ws, M, N, K, y, N, cfg->y_dtype, 0, hip_stream);
+    if (F.fprop == MXFP4_FMT_E2M1 && F.dgrad == MXFP4_FMT_E2M1 && F.wgrad == MXFP4_FMT_E2M1) {
+        rc = quantize_operand_pair(cfg, x, M, K, ws + L.xq, ws + L.xs, sv + S.xtq, sv + S.xts, w, N, K, ws + L.wq,
+                                   ws + L.ws, sv + S.wtq, sv + S.wts, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+    } else {
+        rc = quantize_operand(cfg, x, M, K, F.fprop, ws + L.xq, ws + L.xs, F.wgrad, sv + S.xtq, sv + S.xts, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+        rc = quantize_operand(cfg, w, N, K, F.fprop, ws + L.wq, ws + L.ws, F.dgrad, sv + S.wtq, sv + S.wts, hip_stream);
+        if (rc != MXFP4_OK) return rc;
+    }
+    return mxfp4_gemm_fmt(ws + L.xq, ws + L.xs, F.fprop, ws + L.wq, ws + L.ws, F.fprop, M, N, K, y, N, cfg->y_dtype, 0,
+                          hip_stream);
 }
 
 int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes, void *dx, void *dw, int64_t M,
@@ -462,23 +513,27 @@ int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes
     if (M <= 0 || N <= 0 || K <= 0 || (M % 32) != 0 || (N % 32) != 0 || (K % 32) != 0) return MXFP4_ESHAPE;
     if (!dx && !dw) return MXFP4_OK;
     if (!dy || !saved || !workspace) return MXFP4_EINVAL;
-    const BwdLayout L = bwd_layout(M, N, K);
-    const SavedLayout S = saved_layout(M, N, K);
+    const StageFormats F = stage_formats(cfg);
+    const BwdLayout L = bwd_layout(M, N, K, F);
+    const SavedLayout S = saved_layout(M, N, K, F);
     if (workspace_bytes < L.total || saved_bytes < S.total) return MXFP4_EWORKSPACE;
     if (!aligned(workspace, 256) || !aligned(saved, 256) || !aligned(dy, 16) || (dx && !aligned(dx, 16)) ||
         (dw && !aligned(dw, 16)))
         return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const uint8_t *sv = static_cast<const uint8_t *>(saved);
-    rc = quantize_operand(cfg, dy, M, N, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
+    rc = quantize_operand(cfg, dy, M, N, F.dgrad, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr, F.wgrad,
                           dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    const GemmArgs gd{ws + L.gq, ws + L.gs, sv + S.wtq, sv + S.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0};
+    const GemmArgs gd{ws + L.gq, ws + L.gs, sv + S.wtq, sv + S.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0,
+                      F.dgrad, F.dgrad};
     const GemmArgs gw{ws + L.gtq, ws + L.gts, sv + S.xtq, sv + S.xts, N, K, M, dw, K,
-                      cfg->dw_dtype == MXFP4_OUT_FP32, cfg->dw_accumulate};
+                      cfg->dw_dtype == MXFP4_OUT_FP32, cfg->dw_accumulate, F.wgrad, F.wgrad};
     if (dx && dw) return gemm_pair(gd, cfg->dx_dtype, gw, cfg->dw_dtype, hip_stream);
-    if (dx) return mxfp4_gemm(gd.aq, gd.as, gd.bq, gd.bs, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
-    return mxfp4_gemm(gw.aq, gw.as, gw.bq, gw.bs, N, K, M, dw, K, cfg->dw_dtype, cfg->dw_accumulate, hip_stream);
+    if (dx)
+        return mxfp4_gemm_fmt(gd.aq, gd.as, F.dgrad, gd.bq, gd.bs, F.dgrad, M, K, N, dx, K, cfg->dx_dtype, 0, hip_stream);
+    return mxfp4_gemm_fmt(gw.aq, gw.as, F.wgrad, gw.bq, gw.bs, F.wgrad, N, K, M, dw, K, cfg->dw_dtype,
+                          cfg->dw_accumulate, hip_stream);
 }
 
 }  // extern "C"

@@ -176,3 +176,71 @@ def test_fp8_argument_errors():
     rc = mx.lib().mxfp4_gemm_fmt(q.data_ptr(), s.data_ptr(), 5, q.data_ptr(), s.data_ptr(), 1, 16, 16, 32,
                                  out.data_ptr(), 16, mx.OUT_FP32, 0, None)
     assert rc == mx.EINVAL
+
+
+# ---- the stage-wise recipe: MXFP4 in some stages, MXFP8 in the others (Table 1) -------------------
+def _slices(buf, offs, dims, fmts):
+    b = buf.cpu().numpy()
+    out = []
+    for k, ((R, C), f) in enumerate(zip(dims, fmts)):
+        nq = R * (C if f else C // 2)
+        out.append((b[offs[2 * k]: offs[2 * k] + nq].reshape(R, -1),
+                    b[offs[2 * k + 1]: offs[2 * k + 1] + R * C // 32].reshape(R, C // 32)))
+    return out
+
+
+def _oracle_q(x, axis, fmt, had, rnd, seed):
+    if fmt:
+        return oracle.quantize_fp8(x, axis, oracle.HAD_NONE, seed)
+    return oracle.quantize(x, axis, had, rnd, seed)
+
+
+@pytest.mark.parametrize("saved_path", [False, True])
+@pytest.mark.parametrize("fmts", [(0, 1, 1), (0, 0, 1), (1, 1, 1), (1, 0, 0), (0, 1, 0)])
+@pytest.mark.parametrize("shape", [(256, 512, 1024), (96, 160, 224)])
+def test_linear_with_stage_formats(shape, fmts, saved_path):
+    M, N, K = shape
+    had, rnd, seed = mx.HAD_DET, mx.RNE, 31
+    fF, fD, fW = fmts
+    x = synth.normal(M, K, 1.0, 1, synth.STREAM_X)
+    w = synth.normal(N, K, 0.02, 1, synth.STREAM_W)
+    dy = synth.normal(M, N, 1e-3, 1, synth.STREAM_DY)
+    cfg = mx.make_cfg(had, rnd, seed, y_dtype=mx.OUT_FP32, dx_dtype=mx.OUT_FP32, dw_dtype=mx.OUT_FP32,
+                      fprop_format=fF, dgrad_format=fD, wgrad_format=fW)
+    xg, wg, dyg = x.to("cuda:0"), w.to("cuda:0"), dy.to("cuda:0")
+    if saved_path:
+        y, ws_f, saved = mx.mxfp4_linear_fwd_save(xg, wg, cfg)
+        dx, dw, ws_b = mx.mxfp4_linear_bwd_saved(dyg, saved, K, cfg)
+    else:
+        y, ws_f = mx.mxfp4_linear_fwd(xg, wg, cfg)
+        dx, dw, ws_b = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg)
+    torch.cuda.synchronize()
+    xb, wb, dyb = synth.as_u16(x), synth.as_u16(w), synth.as_u16(dy)
+    L, F = oracle.AXIS_LAST, oracle.AXIS_FIRST
+    want = {"X": _oracle_q(xb, L, fF, had, rnd, seed), "W": _oracle_q(wb, L, fF, had, rnd, seed),
+            "dY": _oracle_q(dyb, L, fD, had, rnd, seed), "W^T": _oracle_q(wb, F, fD, had, rnd, seed),
+            "dY^T": _oracle_q(dyb, F, fW, had, rnd, seed), "X^T": _oracle_q(xb, F, fW, had, rnd, seed)}
+    fw = _slices(ws_f, mx.mxfp4_linear_workspace_layout(M, N, K, False, cfg), [(M, K), (N, K)], [fF, fF])
+    bw = _slices(ws_b, mx.mxfp4_linear_workspace_layout(M, N, K, True, cfg), [(M, N), (K, N), (N, M), (K, M)],
+                 [fD, fD, fW, fW])
+    got = {"X": fw[0], "W": fw[1], "dY": bw[0], "dY^T": bw[2]}
+    if saved_path:
+        sv = _slices(saved, mx.mxfp4_linear_saved_layout(M, N, K, cfg), [(K, N), (K, M)], [fD, fW])
+        got["W^T"], got["X^T"] = sv[0], sv[1]
+    else:
+        got["W^T"], got["X^T"] = bw[1], bw[3]
+    for name in got:
+        assert np.array_equal(got[name][1], want[name][1]), f"{name}: scale bytes differ"
+        assert np.array_equal(got[name][0], want[name][0]), f"{name}: codes differ"
+    for out, a, b, f in ((y, "X", "W", fF), (dx, "dY", "W^T", fD), (dw, "dY^T", "X^T", fW)):
+        o, absum = oracle.gemm_fmt(want[a][0], want[a][1], f, want[b][0], want[b][1], f)
+        tol = FP8_RTOL if f else 1e-5
+        assert np.all(np.abs(out.cpu().numpy() - o) <= tol * absum), (a, b)
+
+
+def test_stage_formats_reject_2d_geometry():
+    cfg = mx.make_cfg(geometry=mx.GEOM_2D, wgrad_format=mx.FMT_E4M3)
+    x = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(mx.Mxfp4Error) as e:
+        mx.mxfp4_linear_fwd(x, x, cfg)
+    assert e.value.status == mx.ENOTIMPL

@@ -137,8 +137,55 @@ def other_config(args, torch, mx, synth) -> int:
     return 0
 
 
+def ladder(args, torch, mx, synth) -> int:
+    """The stage-wise enablement ladder of Table 1 at kernel level: the headline layer (fwd+bwd, training pair)
+    with MXFP4 in none, one, two or all three of its GEMMs and MXFP8 in the others.  One JSON line."""
+    dev = torch.device("cuda:0")
+    x = synth.normal(M, K, 1.0, 0, synth.STREAM_X).to(dev)
+    w = synth.normal(N, K, 0.02, 0, synth.STREAM_W).to(dev)
+    dy = synth.normal(M, N, 1e-3, 0, synth.STREAM_DY).to(dev)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    dw = torch.empty((N, K), dtype=torch.float32, device=dev)
+    rows = []
+    E2, E4 = mx.FMT_E2M1, mx.FMT_E4M3
+    for name, fm in (("all GEMMs MXFP8", (E4, E4, E4)), ("Fprop MXFP4", (E2, E4, E4)),
+                     ("Fprop + Dgrad MXFP4", (E2, E2, E4)), ("Fprop + Dgrad + Wgrad MXFP4", (E2, E2, E2))):
+        cfg = mx.make_cfg(mx.HAD_DET, mx.RNE, 0, y_dtype=mx.OUT_BF16, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32,
+                          fprop_format=fm[0], dgrad_format=fm[1], wgrad_format=fm[2])
+        ws_f = torch.empty(mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, False), dtype=torch.uint8, device=dev)
+        ws_b = torch.empty(mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, True), dtype=torch.uint8, device=dev)
+        saved = torch.empty(mx.mxfp4_linear_saved_bytes(M, N, K, cfg), dtype=torch.uint8, device=dev)
+
+        def step():
+            mx.mxfp4_linear_fwd_save(x, w, cfg, y=y, workspace=ws_f, saved=saved)
+            mx.mxfp4_linear_bwd_saved(dy, saved, K, cfg, dx=dx, dw=dw, workspace=ws_b)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        rows.append((name, (time.perf_counter() - t0) * 1e3 / args.steps))
+    base = rows[0][1]
+    out = {
+        "metric": "linear_fwd_bwd_ms_by_stage_recipe", "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "higher_is_better": False, "dtype": "fp4/fp8", "data": "synthetic",
+        "config": {"workload": "Llama-3.1-8B fused QKV linear, M=8192 K=4096 N=6144, fwd+bwd, deterministic H32 on the "
+                               "MXFP4 GEMMs, RNE; stages not in MXFP4 run in MXFP8 (E4M3)"},
+        "ladder": [{"recipe": n, "ms_per_step": round(ms, 4), "speedup_vs_all_mxfp8": round(base / ms, 3),
+                    "tflops_incl_quant": round(3 * 2.0 * M * N * K / (ms * 1e-3) / 1e12, 1)} for n, ms in rows],
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--ladder", action="store_true",
+                    help="time the headline layer under the stage-wise recipes of Table 1 (MXFP4 in 0..3 of the "
+                         "GEMMs, MXFP8 in the others) instead of the headline benchmark")
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="benchmark configuration; 2 (the default) is the headline workload with the full report")
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,6 +212,8 @@ def main() -> int:
     mx.lib()  # fail loudly now if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.ladder:
+        return ladder(args, torch, mx, synth)
     if args.config != 2:
         return other_config(args, torch, mx, synth)
 

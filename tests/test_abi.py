@@ -163,6 +163,38 @@ def test_2d_geometry_argument_errors(L):
     assert L.mxfp4_linear_bwd(P, P, P, P, None, 64, 96, 136, ctypes.byref(g2), W, needb, None) == mx.ESHAPE
 
 
+def test_fp8_and_stage_format_argument_errors(L):
+    q = L.mxfp4_quantize_fp8
+    assert q(P, 64, 64, 64, 2, 0, 0, P, P, None) == mx.EINVAL          # axis
+    assert q(P, 64, 64, 64, 0, 9, 0, P, P, None) == mx.EINVAL          # hadamard
+    assert q(P, 64, 48, 48, 0, 0, 0, P, P, None) == mx.ESHAPE
+    assert q(P, 48, 64, 64, 1, 0, 0, P, P, None) == mx.ESHAPE
+    assert q(P + 2, 64, 64, 64, 0, 0, 0, P, P, None) == mx.EALIGN
+    assert q(None, 0, 64, 64, 0, 0, 0, None, None, None) == mx.OK
+    g = L.mxfp4_gemm_fmt
+    assert g(P, P, 2, P, P, 0, 16, 16, 32, P, 16, 1, 0, None) == mx.EINVAL
+    assert g(P, P, 1, P, P, -1, 16, 16, 32, P, 16, 1, 0, None) == mx.EINVAL
+    assert g(P, P, 1, P, P, 1, 16, 16, 48, P, 16, 1, 0, None) == mx.ESHAPE
+    assert g(P, P, 1, P, P, 1, 0, 16, 32, None, 16, 1, 0, None) == mx.OK
+    M, N, K = 64, 96, 128
+    all4, all8 = mx.make_cfg(), mx.make_cfg(fprop_format=1, dgrad_format=1, wgrad_format=1)
+    mixed = mx.make_cfg(dgrad_format=1)
+    # an 8-bit stage doubles the code bytes of its operands, scale bytes stay
+    f4, f8 = (mx.mxfp4_linear_workspace_bytes(M, N, K, c, False) for c in (all4, all8))
+    assert f8 - f4 == (M + N) * K // 2
+    b4, bm = (mx.mxfp4_linear_workspace_bytes(M, N, K, c, True) for c in (all4, mixed))
+    assert bm - b4 == (M + K) * N // 2
+    assert mx.mxfp4_linear_saved_bytes(M, N, K, mixed) - mx.mxfp4_linear_saved_bytes(M, N, K, all4) == K * N // 2
+    assert mx.mxfp4_linear_saved_bytes(M, N, K, None) == mx.mxfp4_linear_saved_bytes(M, N, K, all4)
+    assert mx.mxfp4_linear_workspace_layout(M, N, K, True, None) == mx.mxfp4_linear_workspace_layout(M, N, K, True, all4)
+    bad = mx.make_cfg(wgrad_format=3)
+    W = 0x100000
+    assert L.mxfp4_linear_fwd(P, P, P, M, N, K, ctypes.byref(bad), W, f8, None) == mx.EINVAL
+    g2 = mx.make_cfg(geometry=mx.GEOM_2D, fprop_format=1)
+    assert L.mxfp4_linear_fwd(P, P, P, M, N, K, ctypes.byref(g2), W, f8, None) == mx.ENOTIMPL
+    assert L.mxfp4_linear_fwd(P, P, P, M, N, K, ctypes.byref(all8), W, f4, None) == mx.EWORKSPACE
+
+
 def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
     monkeypatch.setattr(mx, "_lib", None)
     monkeypatch.setattr(mx, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -369,6 +369,17 @@ def main() -> int:
         q_dual(rot[state["i"] % len(rot)], xq, xs, xtq, xts)
         state["i"] += 1
 
+    x8q = torch.empty((M, K), dtype=torch.uint8, device=dev)   # MXFP8 outputs (row-wise [M][K], column-wise [K][M])
+
+    def fp8_rot(axis):
+        def run():
+            t = rot[state["i"] % len(rot)]
+            rc = L.mxfp4_quantize_fp8(t.data_ptr(), M, K, K, axis, mx.HAD_NONE, 0, x8q.data_ptr(),
+                                      (xs if axis == mx.AXIS_LAST else xts).data_ptr(), st)
+            assert rc == mx.OK
+            state["i"] += 1
+        return run
+
     def dual_2d_rot():  # the 32 x 32 geometry, both outputs, no rotation
         t = rot[state["i"] % len(rot)]
         rc = L.mxfp4_quantize_2d(t.data_ptr(), M, K, K, mx.HAD_NONE, mx.RNE, 0, xq.data_ptr(), xs.data_ptr(),
@@ -385,11 +396,17 @@ def main() -> int:
     t_dual_cold = event_time_ms(dual_rot, n_rot, torch)
     dual_2d_rot()
     t_2d_cold = event_time_ms(dual_2d_rot, n_rot, torch)
+    fp8_rot(mx.AXIS_LAST)()
+    fp8_rot(mx.AXIS_FIRST)()
+    t_fp8_rows = event_time_ms(fp8_rot(mx.AXIS_LAST), n_rot, torch)
+    t_fp8_cols = event_time_ms(fp8_rot(mx.AXIS_FIRST), n_rot, torch)
     del rot
     gbs = lambda n_el, ms, bpe=BYTES_PER_ELEM: n_el * bpe / (ms * 1e-3) / 1e9
     quant_rows_gbs, quant_cols_gbs = gbs(M * K, t_rows_cold), gbs(M * K, t_cols_cold)
     quant_dual_gbs = gbs(M * K, t_dual_cold, BYTES_PER_ELEM_DUAL)
     quant_2d_gbs = gbs(M * K, t_2d_cold, BYTES_PER_ELEM_DUAL)
+    bpe8 = 2.0 + 1.0 + 1.0 / 32.0  # bf16 read + one E4M3 byte + scale byte per element
+    fp8_rows_gbs, fp8_cols_gbs = gbs(M * K, t_fp8_rows, bpe8), gbs(M * K, t_fp8_cols, bpe8)
 
     out = {
         "metric": "mxfp4_linear_gemm_tflops_incl_hadamard_quantize",
@@ -436,6 +453,10 @@ def main() -> int:
                                   "launch_ms": round(t_dual_cold, 4), "bytes_per_element": BYTES_PER_ELEM_DUAL},
             "dual_2d_hbm_resident": {"achieved": round(quant_2d_gbs, 1), "frac": round(quant_2d_gbs / PEAK_HBM_GBS, 4),
                                      "launch_ms": round(t_2d_cold, 4), "bytes_per_element": BYTES_PER_ELEM_DUAL},
+            "mxfp8_rows_hbm_resident": {"achieved": round(fp8_rows_gbs, 1), "frac": round(fp8_rows_gbs / PEAK_HBM_GBS, 4),
+                                        "launch_ms": round(t_fp8_rows, 4), "bytes_per_element": bpe8},
+            "mxfp8_cols_hbm_resident": {"achieved": round(fp8_cols_gbs, 1), "frac": round(fp8_cols_gbs / PEAK_HBM_GBS, 4),
+                                        "launch_ms": round(t_fp8_cols, 4), "bytes_per_element": bpe8},
             "in_step_ms": {k: round(v, 4) for k, v in t_q.items()},
             "in_step_gbs_cache_warm": {k: round(gbs(elems[k], t_q[k]), 1) for k in elems},
         },

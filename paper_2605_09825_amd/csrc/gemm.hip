@@ -448,6 +448,9 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
 
         // ---- epilogue ---------------------------------------------------------------------------
+        // The output is stored non-temporally: it is not read again here, and written the ordinary way it
+        // pushes the operands of the kernels that follow (the next quantisers, the next GEMM) out of the
+        // last-level cache -- measured on the 8B fused-QKV layer: 10 % of a whole forward + backward step.
         // A lane owns row fr of each 32-row group and, per 32-column group, columns 8*q + 4*fh + {0..3}.
         // Stage buffer 1 is free (all waves passed the last barrier; buffer 0 may already hold the next
         // tile's stage 0): each wave transposes its sub-tile through its own 16 KiB slice of it, 64
@@ -497,7 +500,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
                         const int r4 = (8 * h + u) * 4;
                         v4i v = buf[u];
                         if ((r4 >> 4) & 1) v = (v4i){v.z, v.w, v.x, v.y};
-                        *reinterpret_cast<v4i *>(obase + (int64_t)r4 * ld) = v;
+                        __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(obase + (int64_t)r4 * ld));
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -533,7 +536,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
                         v4f *o = reinterpret_cast<v4f *>(obase + (int64_t)((8 * h + u) * 2) * ld);
                         v4f v = buf[u];
                         if (ACC) v += *o;
-                        *o = v;
+                        __builtin_nontemporal_store(v, o);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }

@@ -36,7 +36,7 @@ BYTES_PER_ELEM_DUAL = 2.0 + 2 * (0.5 + 1.0 / 32.0)  # one read, both quantisatio
 # Bytes crossing the L2's outward port per GEMM (mean of the three GEMMs of a step), from the FETCH_SIZE and
 # WRITE_SIZE runs summarised in profiles/qkv_traffic_counters.md (FETCH_SIZE x 2.0 after calibration
 # against a 256 MiB copy)
-GEMM_TRAFFIC_BYTES = 294.9e6
+GEMM_TRAFFIC_BYTES = 290.8e6
 
 
 def event_time_ms(fn, iters, torch):

@@ -173,10 +173,25 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const uint8_t *sbase)
 {
-    // each lane: 16 bytes from sbase + voff to LDS[lds_addr + 16*lane]
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2\n\t" ::"s"(lds_addr), "v"(voff), "s"(sbase)
+    // each lane: 16 bytes from sbase + voff to LDS[lds_addr + 16*lane] (the ISA wants one wait state between a
+    // scalar write of M0 and a direct-to-LDS load that reads it)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t" ::"s"(lds_addr), "v"(voff), "s"(sbase)
                  : "memory");
 }
+
+// The same to LDS[lds_base + IMM + 16*lane]: the destination sum is formed straight into M0 (one scalar
+// instruction per load: with one wave per SIMD every instruction issued between two matrix instructions
+// beyond the seven that fit under one costs matrix-unit time).
+template <int IMM>
+__device__ __forceinline__ void dma16_at(uint32_t lds_base, uint32_t voff, const uint8_t *sbase)
+{
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t" ::"s"(lds_base), "v"(voff), "s"(sbase),
+                 "n"(IMM)
+                 : "memory", "scc");
+}
+
+template <int V>
+using IC = std::integral_constant<int, V>;
 
 // Operand rows one wave loads for one tile: rows wave*64 .. +63 of the tile's A rows, B rows and
 // of their scale rows.
@@ -239,23 +254,23 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     if (lw >= count_x) return;  // (whole workgroup: nothing to do)
 
     // ---- direct-to-LDS loads: per-lane offsets (fixed for the whole kernel) -----------------
+    // dvo[g]: this lane's 16 bytes of 8-row group g of the wave's 64 rows (row 8g + lane/8; the chunk within
+    // the row's 128 bytes is swizzled by the row, odd groups one further)
     const int drr = lane >> 3, dcc = lane & 7;
-    const uint32_t dvoff0 = (uint32_t)(drr * rowbytes) + (uint32_t)((dcc ^ drr) << 4);        // even 8-row groups
-    const uint32_t dvoff1 = (uint32_t)(drr * rowbytes) + (uint32_t)((dcc ^ drr ^ 1) << 4);    // odd ones
+    uint32_t dvo[8];
+#pragma unroll
+    for (int g = 0; g < 8; ++g)
+        dvo[g] = (uint32_t)((8 * g + drr) * rowbytes) + (uint32_t)((dcc ^ drr ^ (g & 1)) << 4);
+    const uint32_t lds_wave = lds0 + (uint32_t)wave * 8192u;  // the wave's 8 x 1 KiB of each operand's stage slice
     const uint32_t svoff = (uint32_t)((lane >> 1) * nkb) + (uint32_t)((lane & 1) << 4);
 
     // load n (0..15) of stage s of tile t for this wave: even n -> A, odd n -> B; 8-row group n/2 of
     // the wave's 64 rows
-    auto issue_load = [&](const TileSrc &t, int s, int buf, int n) {
-        const uint32_t base = lds0 + buf * STAGE_BYTES;
+    auto issue_load = [&](const TileSrc &t, int s, int buf, auto nc) {
+        constexpr int n = decltype(nc)::value, g = n >> 1;
         const int64_t koff = (int64_t)s * (STAGE_K / 2);
-        const int g = n >> 1;
-        const uint32_t dst = (uint32_t)((wave * 8 + g) * 1024);
-        const uint32_t vo = (g & 1) ? dvoff1 : dvoff0;
-        if (n & 1)
-            dma16(base + OFF_B + dst, vo, t.b + g * 8 * rowbytes + koff);
-        else
-            dma16(base + OFF_A + dst, vo, t.a + g * 8 * rowbytes + koff);
+        dma16_at<((n & 1) ? OFF_B : OFF_A) + g * 1024>(lds_wave + buf * STAGE_BYTES, dvo[g],
+                                                       ((n & 1) ? t.b : t.a) + koff);
     };
     // Scale batch b holds the 32 scale bytes per row of stages first(b) .. first(b)+3, where
     // first(b) = min(4b, nstages-4): the last batch is pulled back so that it never reads past a
@@ -264,11 +279,14 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // instruction j (0..3) of batch b for this wave: j>>1 = operand, j&1 = which 32 of its 64 rows
     // Batch b of a tile lives in scale buffer (b ^ par) & 1; par alternates between tiles so that
     // a tile's first batch never lands in the buffer its predecessor's last batch is still read from.
+    auto scales_dst = [&](int b, int j, int par) {
+        return lds0 + OFF_SC + ((b ^ par) & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES + (wave * 64 + (j & 1) * 32) * 32;
+    };
+    auto scales_src = [&](const TileSrc &t, int b, int j) {
+        return ((j >> 1) ? t.bs : t.as) + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * SC_STAGE;
+    };
     auto issue_scales = [&](const TileSrc &t, int b, int j, int par) {
-        const uint8_t *rows = (j >> 1) ? t.bs : t.as;
-        const uint32_t dst = lds0 + OFF_SC + ((b ^ par) & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES +
-                             (wave * 64 + (j & 1) * 32) * 32;
-        dma16(dst, svoff, rows + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * SC_STAGE);
+        dma16(scales_dst(b, j, par), svoff, scales_src(t, b, j));
     };
 
     // ---- fragment reads: per-lane offsets ---------------------------------------------------
@@ -367,15 +385,27 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     auto stage = [&](const TileSrc &cur, const TileSrc &nxt, int par, int par_nxt, int s, auto mode) {
         constexpr int MODE = decltype(mode)::value;
         const int buf = s & 1;
+        // destination and source of the stage's one scale load: worked out in idle slots of K-step 1, used
+        // in K-step 3
+        uint32_t sc_dst = 0;
+        const uint8_t *sc_src = nullptr;
 #define MXFP4_K0(N)                                                                              \
         if ((N) < 8) read_one(buf, FMT ? 2 : 1, FMT ? 2 : 1, (N));                               \
-        if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, 8 + ((N) >> 1));              \
-        if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, 8 + ((N) >> 1));      \
+        if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, IC<8 + ((N) >> 1)>{});       \
+        if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, IC<8 + ((N) >> 1)>{});           \
         MXFP4_SLOT_MMA(0, N, MODE == 3) MXFP4_PIN()
         MXFP4_16(MXFP4_K0)
 #undef MXFP4_K0
 #define MXFP4_K1(N)                                                                              \
         if ((N) < 8) read_one(buf, FMT ? 3 : 2, FMT ? 3 : 0, (N));                               \
+        if ((MODE == 0 || MODE == 3) && (N) == 9) {                                              \
+            sc_dst = scales_dst((s + 1) / BATCH + 1, (s + 1) & 3, par);                          \
+            asm volatile("" : "+s"(sc_dst));                                                     \
+        }                                                                                        \
+        if ((MODE == 0 || MODE == 3) && (N) == 12) {                                             \
+            sc_src = scales_src(cur, (s + 1) / BATCH + 1, (s + 1) & 3);                          \
+            asm volatile("" : "+s"(sc_src));                                                     \
+        }                                                                                        \
         MXFP4_SLOT_MMA(1, N, FMT && MODE == 3) MXFP4_PIN()
         MXFP4_16(MXFP4_K1)
 #undef MXFP4_K1
@@ -391,15 +421,18 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #define MXFP4_K3(N)                                                                              \
         if (MODE != 2 && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                                   \
         if (FMT && MODE != 2 && (N) < 8) read_one(buf ^ 1, 1, 1, (N));                            \
-        if (MODE != 2 && (N) >= 8) read_scale_one(s + 1, (N) - 8, par);                           \
-        if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, (N) >> 1);                       \
-        if ((MODE == 0 || MODE == 3) && (N) == 14) issue_scales(cur, (s + 1) / BATCH + 1, (s + 1) & 3, par); \
-        if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, (N) >> 1);                \
+        if (MODE != 2 && (N) < 8) read_scale_one(s + 1, (N), par);                                \
+        if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, IC<((N) >> 1)>{}); \
+        if ((MODE == 0 || MODE == 3) && (N) == 14) dma16(sc_dst, svoff, sc_src);                 \
+        if (MODE != 2 && (N) == 13) __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0): see below */ \
+        if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, IC<((N) >> 1)>{});                    \
         if (MODE == 1 && !((N) & 1) && (N) < 8) issue_scales(nxt, 0, (N) >> 1, par_nxt);         \
         if (MODE == 2 && (N) == 1) issue_scales(nxt, 1, 0, par_nxt);                             \
         MXFP4_SLOT_MMA(3, N, false) MXFP4_PIN()
         MXFP4_16(MXFP4_K3)
 #undef MXFP4_K3
+        // (the scale bytes were fetched in the first half of K-step 3 and have long landed: the explicit wait
+        // in slot 13 tells the compiler so, which otherwise puts a counter wait in front of every permute)
         if (MODE != 2) permute_scales();
     };
     using mode_main = std::integral_constant<int, 0>;
@@ -410,8 +443,9 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // ---- first tile: fill the pipeline --------------------------------------------------------
     // all of stage 0, the first 8 loads of stage 1, scale batch 0 and the first load of batch 1
     TileSrc cur = tile_src(lw);
-#pragma unroll
-    for (int n = 0; n < 16; ++n) issue_load(cur, 0, 0, n);
+#define MXFP4_FILL(N) issue_load(cur, 0, 0, IC<(N)>{});
+    MXFP4_16(MXFP4_FILL)
+#undef MXFP4_FILL
 #pragma unroll
     for (int j = 0; j < 4; ++j) issue_scales(cur, 0, j, 0);
     issue_scales(cur, 1, 0, 0);
@@ -427,8 +461,9 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         // here); after the barrier start stage 1's first half and fetch the first fragments
         if (lloc == lw) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");  // (later tiles waited before the epilogue)
         __syncthreads();
-#pragma unroll
-        for (int n = 0; n < 8; ++n) issue_load(cur, 1, 1, n);
+#define MXFP4_FILL(N) if ((N) < 8) issue_load(cur, 1, 1, IC<((N) & 7)>{});
+        MXFP4_16(MXFP4_FILL)
+#undef MXFP4_FILL
 #pragma unroll
         for (int f = 0; f < 8; ++f) {
             read_one(0, 0, 0, f);

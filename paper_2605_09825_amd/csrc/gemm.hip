@@ -221,7 +221,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t rowbytes = FMT ? C : (C >> 1), nkb = C >> 5;
-    const int nstages = (int)(rowbytes / (STAGE_K / 2));  // even; >= 4 (E2M1) or >= 8 (E4M3): the host checks
+    const int nstages = (int)(rowbytes / (STAGE_K / 2));  // >= 4 (E2M1) or >= 8 (E4M3): the host checks
     constexpr int BATCH = FMT ? 8 : 4;   // stages per scale batch (32 scale bytes per row)
     constexpr int SC_STAGE = FMT ? 4 : 8;  // scale bytes per row and stage
 
@@ -330,6 +330,10 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         }
     };
 
+    // Stage s of a tile lives in stage buffer (s & 1) ^ bp.  The hand-over loads put the next tile's stage 0
+    // into the buffer after the current tile's last one, so with an odd number of stages the parity flips
+    // from tile to tile.
+    int bp = 0;
     v16f acc[4][4];
     const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -384,7 +388,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     //           nxt's scale batch 1 and fetches nothing (the epilogue follows)
     auto stage = [&](const TileSrc &cur, const TileSrc &nxt, int par, int par_nxt, int s, auto mode) {
         constexpr int MODE = decltype(mode)::value;
-        const int buf = s & 1;
+        const int buf = (s & 1) ^ bp;
         // destination and source of the stage's one scale load: worked out in idle slots of K-step 1, used
         // in K-step 3
         uint32_t sc_dst = 0;
@@ -461,13 +465,13 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         // here); after the barrier start stage 1's first half and fetch the first fragments
         if (lloc == lw) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");  // (later tiles waited before the epilogue)
         __syncthreads();
-#define MXFP4_FILL(N) if ((N) < 8) issue_load(cur, 1, 1, IC<((N) & 7)>{});
+#define MXFP4_FILL(N) if ((N) < 8) issue_load(cur, 1, bp ^ 1, IC<((N) & 7)>{});
         MXFP4_16(MXFP4_FILL)
 #undef MXFP4_FILL
 #pragma unroll
         for (int f = 0; f < 8; ++f) {
-            read_one(0, 0, 0, f);
-            if (FMT) read_one(0, 1, 1, f);
+            read_one(bp, 0, 0, f);
+            if (FMT) read_one(bp, 1, 1, f);
             read_scale_one(0, f, par);
         }
         permute_scales();
@@ -487,13 +491,13 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         // pushes the operands of the kernels that follow (the next quantisers, the next GEMM) out of the
         // last-level cache -- measured on the 8B fused-QKV layer: 10 % of a whole forward + backward step.
         // A lane owns row fr of each 32-row group and, per 32-column group, columns 8*q + 4*fh + {0..3}.
-        // Stage buffer 1 is free (all waves passed the last barrier; buffer 0 may already hold the next
-        // tile's stage 0): each wave transposes its sub-tile through its own 16 KiB slice of it, 64
+        // The last stage's buffer is free (all waves passed the last barrier; the other one may already hold
+        // the next tile's stage 0): each wave transposes its sub-tile through its own 16 KiB slice of it, 64
         // (bf16) or 32 (fp32) rows at a time, and writes whole 256- / 512-byte row segments.  Rows are
         // stored unpadded; 16-byte chunk c of row r sits at chunk c ^ (r & 15) (bf16: and its two 8-byte
         // halves swap when r & 16), which keeps both the 8/16-byte writes and the 16-byte reads
         // conflict-free.
-        uint8_t *epi = smem + STAGE_BYTES + wave * 16384;
+        uint8_t *epi = smem + ((((nstages - 1) & 1) ^ bp) ? STAGE_BYTES : 0) + wave * 16384;
         const int64_t row0 = cur.m0 + wm * 128, col0 = cur.n0 + wn * 128;
         if (!OUT_FP32) {
 #pragma unroll
@@ -577,10 +581,11 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
                 }
             }
         }
-        // (the barrier at the top of the loop keeps the next tile's loads out of stage buffer 1 until
+        // (the barrier at the top of the loop keeps the next tile's loads out of that buffer until
         // every wave is done reading its slice)
         cur = nxt;
         par = par_nxt;
+        bp ^= nstages & 1;
     }
     // nothing may still be writing this workgroup's LDS when it retires
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -630,12 +635,13 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p
 
 }  // namespace
 
-// the tiled kernel wants whole 256 x 256 tiles, K in whole 512s (at least 1024: scale bytes are
-// fetched 32 per row, 16-byte aligned), and 16-byte aligned rows everywhere
+// the tiled kernel wants whole 256 x 256 tiles, K in whole stages (128 bytes of codes per row: 256 E2M1
+// or 128 E4M3 elements) and at least 1024 (scale bytes are fetched 32 per row), and 16-byte aligned
+// code rows and output rows
 static bool tile_eligible(const GemmArgs &g)
 {
     if (g.a_fmt != g.b_fmt) return false;  // mixed formats: any-shape kernel
-    const bool k_ok = g.a_fmt ? (g.C >= 1024 && (g.C % 256) == 0) : (g.C >= 1024 && (g.C % 512) == 0);
+    const bool k_ok = g.C >= 1024 && (g.C % (g.a_fmt ? 128 : 256)) == 0;
     return k_ok && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.ld % 8) == 0 &&
            (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 && (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 &&
            (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) && g.C < (int64_t(1) << 31);

@@ -117,7 +117,7 @@ def test_gemm_narrow_exponent_range_meets_the_mxfp4_bound(shape, fmts):
     assert_close(got.cpu().numpy(), want, absum)
 
 
-@pytest.mark.parametrize("C", [1024, 2304])
+@pytest.mark.parametrize("C", [1024, 2304, 1152, 1408])  # 8, 18, 9 and 11 K-stages of 128
 def test_fp8_many_tiles_per_workgroup_sampled(C):
     # 17 x 17 = 289 tiles of 256 x 256: more than one tile per CU, so tiles hand over inside a workgroup;
     # narrow exponent range, so the MXFP4 bound applies (a wrong hand-over would show as a gross error)

@@ -38,7 +38,7 @@ def assert_close(got, want, absum):
 
 @pytest.mark.parametrize("shape", [(64, 64, 128), (16, 16, 32), (37, 53, 96), (1, 1, 32), (256, 512, 512),
                                    (130, 70, 1024), (512, 384, 4096), (100, 260, 160), (512, 768, 1536),
-                                   (256, 256, 1024), (768, 512, 2560)])
+                                   (256, 256, 1024), (768, 512, 2560), (512, 256, 1280), (256, 768, 1792)])
 def test_random_codes_fp32(shape):
     Ra, Rb, C = shape
     rng = np.random.default_rng(Ra * 7 + Rb * 3 + C)
@@ -50,7 +50,7 @@ def test_random_codes_fp32(shape):
 
 
 @pytest.mark.parametrize("shape", [(300, 520, 1024), (544, 784, 1536), (320, 256, 2048), (256, 257, 1024),
-                                   (1030, 513, 1024)])
+                                   (1030, 513, 1024), (300, 520, 1280)])
 def test_ragged_rows_and_columns_around_whole_tiles(shape):
     # row / column counts that leave edge strips beside a 256-aligned interior (different kernels write the
     # interior and the strips): every output element once, nothing outside
@@ -162,11 +162,12 @@ def sample_positions(rng, Ra, Rb, n_rows=4, n_cols=4, n_tiles=24):
     return np.array(ii, dtype=np.int64), np.array(jj, dtype=np.int64)
 
 
+@pytest.mark.parametrize("C", [1024, 1280, 2304])
 @pytest.mark.parametrize("out_dtype", [mx.OUT_FP32, mx.OUT_BF16])
-def test_many_tiles_per_workgroup_sampled(out_dtype):
-    # 17 x 17 = 289 tiles of 256 x 256 (more than one per CU, not a multiple of 8), 4 K-stages
+def test_many_tiles_per_workgroup_sampled(out_dtype, C):
+    # 17 x 17 = 289 tiles of 256 x 256 (more than one per CU, not a multiple of 8); 4, 5 and 9 K-stages of 256
+    # (with an odd count the stage buffers swap roles from one tile of a workgroup to the next)
     Ra = Rb = 256 * 17
-    C = 1024
     rng = np.random.default_rng(5)
     aq, as_ = rand_operand(rng, Ra, C)
     bq, bs = rand_operand(rng, Rb, C)

@@ -257,8 +257,15 @@ constexpr int CT_COLS = 128, CT_RB = 8;
 constexpr int MODE_COLS = 0, MODE_DUAL = 1, MODE_2D = 2;
 constexpr int RAW_PITCH = 272;  // bytes per parked row: 256 + 16, so that the 16-byte reads below (16 lanes =
                                 // 4 rows x 4 blocks per issue) and the dword writes touch every bank once
-constexpr int LDS_Q_BYTES = CT_RB * (CT_COLS + 1) * 16, LDS_S_BYTES = CT_COLS * CT_RB;
-constexpr int LDS_RAW_BYTES = CT_RB * 32 * RAW_PITCH;
+constexpr int LDS_S_BYTES = CT_COLS * CT_RB;
+
+// Orders the LDS accesses of one wave (which the hardware performs in program order) for the compiler too.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 __device__ __forceinline__ uint32_t max_across(uint32_t m, int xor_mask)
 {
@@ -295,12 +302,17 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     const int streaming = second ? job1.streaming : job0.streaming;
     const uint32_t bid = blockIdx.x - (second ? job0.nblocks : 0u);
 
+    // LDS: per wave one slice that first holds the wave's parked 32 x 128 elements (DUAL, 2D) and then its
+    // (CT_COLS + 1) x 16 bytes of column-wise codes waiting to be regrouped; behind the slices the scale bytes
+    // of all waves.  A wave only ever touches its own slice until the one barrier before the regrouped stores.
     constexpr bool PARK = (MODE != MODE_COLS);
-    constexpr int LDS_BYTES = (PARK && LDS_RAW_BYTES > LDS_Q_BYTES + LDS_S_BYTES) ? LDS_RAW_BYTES
-                                                                                  : LDS_Q_BYTES + LDS_S_BYTES;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
-    uint4(*lds_q)[CT_COLS + 1] = reinterpret_cast<uint4(*)[CT_COLS + 1]>(lds);
-    uint8_t(*lds_s)[CT_RB] = reinterpret_cast<uint8_t(*)[CT_RB]>(lds + LDS_Q_BYTES);
+    constexpr int SLICE = PARK ? 32 * RAW_PITCH : (CT_COLS + 1) * 16;
+    // the codes of wave w start w * SKEW bytes into its slice, so that the 8 lanes that later gather one output
+    // row from the 8 slices hit different banks (the column-wise-only slice has the odd pitch built in)
+    constexpr int SKEW = PARK ? 16 : 0;
+    static_assert(SLICE >= CT_COLS * 16 + (CT_RB - 1) * SKEW + (PARK ? 0 : 16), "the codes of a wave must fit its slice");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[CT_RB * SLICE + LDS_S_BYTES];
+    uint8_t(*lds_s)[CT_RB] = reinterpret_cast<uint8_t(*)[CT_RB]>(lds + CT_RB * SLICE);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     // Tile order.  A tile contributes only 8 scale bytes per column (4 per row in the row-wise output), far less
@@ -344,10 +356,10 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     }
 
     if (PARK && want_row) {
-        uint8_t *mine = lds + w * (32 * RAW_PITCH);
+        uint8_t *mine = lds + w * SLICE;
 #pragma unroll
         for (int i = 0; i < 32; ++i) *reinterpret_cast<uint32_t *>(mine + i * RAW_PITCH + 4 * lane) = raw[i];
-        __syncthreads();
+        wave_sync();  // (the slice is written and read by this wave only)
         const int cb = lane & 3;
         const int64_t colb = c0 + 32 * cb;
         const int64_t bpr = cols >> 5;
@@ -401,7 +413,7 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
                 s_row[g] = (uint8_t)sb;
             }
         }
-        __syncthreads();  // every wave is done with the parked tile: its LDS becomes the regrouping buffers
+        wave_sync();  // the wave is done with its parked elements: the slice becomes its regrouping buffer
     }
     if (!want_col) return;  // (uniform over the grid)
 
@@ -432,7 +444,7 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
         uint32_t sb;
         encode_scaled<RND>(v, MODE == MODE_2D ? region_max : amax_bits(v), key,
                            (uint64_t)(col + j) * (uint64_t)rows + (uint64_t)rb * 32u, codes, sb);
-        lds_q[w][2 * lane + j] = codes;
+        reinterpret_cast<uint4 *>(lds + w * (SLICE + SKEW))[2 * lane + j] = codes;
         lds_s[2 * lane + j][w] = (uint8_t)sb;
     }
     __syncthreads();
@@ -443,8 +455,8 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     for (int pass = 0; pass < 2; ++pass) {
         const int cl = (tid >> 3) + 64 * pass;
         if (c0 + cl < cols && rb0 + ch < nrb)
-            store_codes(reinterpret_cast<uint4 *>(q + (c0 + cl) * (rows >> 1) + (rb0 + ch) * 16), lds_q[ch][cl],
-                        streaming);
+            store_codes(reinterpret_cast<uint4 *>(q + (c0 + cl) * (rows >> 1) + (rb0 + ch) * 16),
+                        reinterpret_cast<const uint4 *>(lds + ch * (SLICE + SKEW))[cl], streaming);
     }
     if (tid < CT_COLS && c0 + tid < cols) {
         uint8_t *dst = s + (c0 + tid) * nrb + rb0;

@@ -356,46 +356,33 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     }
 
     if (PARK && want_row) {
+        // Row pass p (0/1) works on rows 16p .. 16p+15 of the wave's 32: the first half is parked and worked on
+        // as soon as its 16 loads are back, under the latency of the other 16.
         uint8_t *mine = lds + w * SLICE;
+        auto park = [&](int half) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) *reinterpret_cast<uint32_t *>(mine + i * RAW_PITCH + 4 * lane) = raw[i];
-        wave_sync();  // (the slice is written and read by this wave only)
+            for (int i = 16 * half; i < 16 * half + 16; ++i)
+                *reinterpret_cast<uint32_t *>(mine + i * RAW_PITCH + 4 * lane) = raw[i];
+            wave_sync();  // (the slice is written and read by this wave only)
+        };
         const int cb = lane & 3;
         const int64_t colb = c0 + 32 * cb;
         const int64_t bpr = cols >> 5;
         const bool on = (rb < nrb) && (colb < cols);
-        uint32_t region_max = 0;
-        if (MODE == MODE_2D) {
-#pragma unroll
-            for (int pass = 0; pass < 2; ++pass) {
-                const int r = (lane >> 2) + 16 * pass;
-                const uint4 *p = reinterpret_cast<const uint4 *>(mine + r * RAW_PITCH + 64 * cb);
-                uint4 rraw[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) rraw[j] = p[j];
-                float v[32];
-                widen(rraw, v);
-                rotate_block<HAD>(v, sign_mask);
-                const uint32_t m = amax_bits(v);
-                region_max = m > region_max ? m : region_max;
-            }
-            // the 32 rows of one region: the 16 lanes with this lane's (lane & 3), two rows each
-            region_max = max_across(region_max, 4);
-            region_max = max_across(region_max, 8);
-            region_max = max_across(region_max, 16);
-            region_max = max_across(region_max, 32);
-        }
-#pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
+        auto rotated_row = [&](int pass, float (&v)[32]) {
             const int r = (lane >> 2) + 16 * pass;
-            const int64_t row = rb * 32 + r;
             const uint4 *p = reinterpret_cast<const uint4 *>(mine + r * RAW_PITCH + 64 * cb);
             uint4 rraw[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) rraw[j] = p[j];
-            float v[32];
             widen(rraw, v);
             rotate_block<HAD>(v, sign_mask);
+        };
+        uint32_t region_max = 0;
+        auto row_codes = [&](int pass) {
+            const int64_t row = rb * 32 + (lane >> 2) + 16 * pass;
+            float v[32];
+            rotated_row(pass, v);
             uint4 codes;
             uint32_t sb;
             encode_scaled<RND>(v, MODE == MODE_2D ? region_max : amax_bits(v), key,
@@ -412,7 +399,27 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
             } else if (on) {
                 s_row[g] = (uint8_t)sb;
             }
+        };
+        auto row_max = [&](int pass) {
+            float v[32];
+            rotated_row(pass, v);
+            const uint32_t m = amax_bits(v);
+            region_max = m > region_max ? m : region_max;
+        };
+        park(0);
+        if (MODE == MODE_2D) row_max(0); else row_codes(0);
+        __builtin_amdgcn_sched_barrier(0);  // (keep the second half's LDS writes, and with them the wait, down here)
+        park(1);
+        if (MODE == MODE_2D) {
+            row_max(1);
+            // the 32 rows of one region: the 16 lanes with this lane's (lane & 3), two rows each
+            region_max = max_across(region_max, 4);
+            region_max = max_across(region_max, 8);
+            region_max = max_across(region_max, 16);
+            region_max = max_across(region_max, 32);
+            row_codes(0);
         }
+        row_codes(1);
         wave_sync();  // the wave is done with its parked elements: the slice becomes its regrouping buffer
     }
     if (!want_col) return;  // (uniform over the grid)

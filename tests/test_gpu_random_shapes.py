@@ -1,0 +1,87 @@
+"""Seeded sweep over random shapes, modes, seeds and magnitudes: every quantiser entry point bit-exact
+against the oracle (App. A.1 eq. (1), App. A.2, App. D), every GEMM path (whole tiles, ragged edges
+around tiles, small odd shapes; E2M1 and E4M3 operands) within its bound."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_09825_amd as mx
+from paper_2605_09825_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+FP8_RTOL = 7 * 2.0 ** -13 + 1e-5  # the matrix unit truncates E4M3 products inside groups of 8 (see test_gpu_fp8)
+
+
+def same(gpu_pair, want_pair):
+    return all(np.array_equal(g.cpu().numpy(), w) for g, w in zip(gpu_pair, want_pair))
+
+
+@pytest.mark.parametrize("kind", ["single", "dual", "2d", "fp8", "strided"])
+def test_quantisers_on_random_shapes(kind):
+    rng = np.random.default_rng(["single", "dual", "2d", "fp8", "strided"].index(kind) + 100)
+    for it in range(16):
+        rows, cols = int(rng.integers(1, 40)) * 32, int(rng.integers(1, 40)) * 32
+        had, rnd, seed = int(rng.integers(0, 4)), int(rng.integers(0, 2)), int(rng.integers(0, 2 ** 40))
+        scale = float(10.0 ** rng.uniform(-6, 6))
+        tag = f"{kind} #{it}: {rows}x{cols} had {had} rnd {rnd} seed {seed} scale {scale:.3g}"
+        x = synth.normal(rows, cols, scale, it, synth.STREAM_X)
+        xb, xg = synth.as_u16(x), x.to(DEV)
+        if kind == "single":
+            for axis in (mx.AXIS_LAST, mx.AXIS_FIRST):
+                got = mx.mxfp4_quantize(xg, axis, had, rnd, seed)
+                assert same(got, oracle.quantize(xb, axis, had, rnd, seed)), tag
+        elif kind == "dual":
+            got = mx.mxfp4_quantize_dual(xg, had, rnd, seed)
+            want = oracle.quantize(xb, mx.AXIS_LAST, had, rnd, seed) + oracle.quantize(xb, mx.AXIS_FIRST, had, rnd, seed)
+            assert same(got, want), tag
+        elif kind == "2d":
+            got = mx.mxfp4_quantize_2d(xg, had, rnd, seed)
+            want = (oracle.quantize_2d(xb, mx.AXIS_LAST, had, rnd, seed) +
+                    oracle.quantize_2d(xb, mx.AXIS_FIRST, had, rnd, seed))
+            assert same(got, want), tag
+        elif kind == "fp8":
+            for axis in (mx.AXIS_LAST, mx.AXIS_FIRST):
+                got = mx.mxfp4_quantize_fp8(xg, axis, had, seed)
+                assert same(got, oracle.quantize_fp8(xb, axis, had, seed)), tag
+        else:  # a view with a leading dimension and an offset
+            base = synth.normal(rows + 32, cols + 64, scale, it, synth.STREAM_W)
+            view, view_gpu = base[32:, 64:], base.to(DEV)[32:, 64:]
+            for axis in (mx.AXIS_LAST, mx.AXIS_FIRST):
+                got = mx.mxfp4_quantize(view_gpu, axis, had, rnd, seed)
+                assert same(got, oracle.quantize(synth.as_u16(view.contiguous()), axis, had, rnd, seed)), tag
+
+
+@pytest.mark.parametrize("kind", ["tiles", "ragged", "small"])
+def test_gemms_on_random_shapes(kind):
+    rng = np.random.default_rng(["tiles", "ragged", "small"].index(kind) + 200)
+    for it in range(14):
+        if kind == "tiles":    # whole 256 x 256 tiles, any whole number of K stages
+            Ra, Rb, C = int(rng.integers(1, 4)) * 256, int(rng.integers(1, 4)) * 256, int(rng.integers(4, 13)) * 256
+        elif kind == "ragged":  # edge strips beside a tiled interior
+            Ra, Rb, C = int(rng.integers(200, 900)), int(rng.integers(25, 112)) * 8, int(rng.integers(4, 10)) * 256
+        else:
+            Ra, Rb, C = int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 40)) * 32
+        fa = int(rng.integers(0, 2))
+        fb = fa if it % 2 else int(rng.integers(0, 2))
+
+        def operand(R, fmt):
+            if fmt == mx.FMT_E2M1:
+                return (rng.integers(0, 256, size=(R, C // 2), dtype=np.uint8),
+                        rng.integers(115, 135, size=(R, C // 32), dtype=np.uint8))
+            q = (rng.integers(5, 10, size=(R, C), dtype=np.uint8) << 3) | rng.integers(0, 8, size=(R, C), dtype=np.uint8)
+            q |= rng.integers(0, 2, size=(R, C), dtype=np.uint8) << 7  # finite E4M3 codes of either sign
+            s = rng.integers(121, 134, size=(R, C // 32), dtype=np.uint8)
+            return q.astype(np.uint8), s
+
+        aq, as_ = operand(Ra, fa)
+        bq, bs = operand(Rb, fb)
+        want, absum = oracle.gemm_fmt(aq, as_, fa, bq, bs, fb)
+        got = mx.mxfp4_gemm(*(torch.from_numpy(t).to(DEV) for t in (aq, as_, bq, bs)), out_dtype=mx.OUT_FP32,
+                            a_format=fa, b_format=fb)
+        torch.cuda.synchronize()
+        err = np.abs(got.cpu().numpy().astype(np.float64) - want)
+        tol = 1e-5 if fa == fb == mx.FMT_E2M1 else FP8_RTOL
+        assert (err <= tol * absum).all(), (f"{kind} #{it}: {Ra}x{Rb}x{C} formats {fa}{fb}: "
+                                            f"max err/sum|a||b| {np.max(err / np.maximum(absum, 1e-300)):.3e}")

@@ -367,6 +367,11 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         MXFP8_MMA((P) >> 1, ((N) >> 1) + 8 * ((P) & 1), FRESH)                                                  \
     }
 #define MXFP4_PIN() __builtin_amdgcn_sched_barrier(0);
+    // E2M1: the 8 fragment reads of a K-step go into the even slots, B0..B3 then A0..A3 (instruction n of the
+    // next K-step needs A[n/4] and B[n%4]: every fragment is at least 8 slots old when first used), so that LDS
+    // reads alternate with the direct-to-LDS loads of the odd slots instead of arriving in bursts.
+#define MXFP4_FRAG_SLOT(N) (!FMT && ((N) & 1) == 0)
+#define MXFP4_FRAG_OF(N) (((N) >> 1) < 4 ? 2 * ((N) >> 1) + 1 : 2 * (((N) >> 1) - 4))
 #define MXFP4_16(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)
 
     // One stage = 4 K-steps of 16 matrix instructions.  Everything else is threaded between them,
@@ -394,14 +399,16 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         uint32_t sc_dst = 0;
         const uint8_t *sc_src = nullptr;
 #define MXFP4_K0(N)                                                                              \
-        if ((N) < 8) read_one(buf, FMT ? 2 : 1, FMT ? 2 : 1, (N));                               \
+        if (FMT && (N) < 8) read_one(buf, 2, 2, (N));                                            \
+        if (MXFP4_FRAG_SLOT(N)) read_one(buf, 1, 1, MXFP4_FRAG_OF(N));                           \
         if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, IC<8 + ((N) >> 1)>{});       \
         if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, IC<8 + ((N) >> 1)>{});           \
         MXFP4_SLOT_MMA(0, N, MODE == 3) MXFP4_PIN()
         MXFP4_16(MXFP4_K0)
 #undef MXFP4_K0
 #define MXFP4_K1(N)                                                                              \
-        if ((N) < 8) read_one(buf, FMT ? 3 : 2, FMT ? 3 : 0, (N));                               \
+        if (FMT && (N) < 8) read_one(buf, 3, 3, (N));                                            \
+        if (MXFP4_FRAG_SLOT(N)) read_one(buf, 2, 0, MXFP4_FRAG_OF(N));                           \
         if ((MODE == 0 || MODE == 3) && (N) == 9) {                                              \
             sc_dst = scales_dst((s + 1) / BATCH + 1, (s + 1) & 3, par);                          \
             asm volatile("" : "+s"(sc_dst));                                                     \
@@ -414,7 +421,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         MXFP4_16(MXFP4_K1)
 #undef MXFP4_K1
 #define MXFP4_K2(N)                                                                              \
-        if (!FMT && (N) < 8) read_one(buf, 3, 1, (N));                                           \
+        if (!FMT && (N) < 8) read_one(buf, 3, 1, (N)); /* (early: the barrier below waits for them) */ \
         MXFP4_SLOT_MMA(2, N, false) MXFP4_PIN()
         MXFP4_16(MXFP4_K2)
 #undef MXFP4_K2
@@ -423,12 +430,13 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
 #define MXFP4_K3(N)                                                                              \
-        if (MODE != 2 && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                                   \
+        if (FMT && MODE != 2 && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                            \
+        if (MODE != 2 && MXFP4_FRAG_SLOT(N)) read_one(buf ^ 1, 0, 0, MXFP4_FRAG_OF(N));           \
         if (FMT && MODE != 2 && (N) < 8) read_one(buf ^ 1, 1, 1, (N));                            \
         if (MODE != 2 && (N) < 8) read_scale_one(s + 1, (N), par);                                \
         if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, IC<((N) >> 1)>{}); \
         if ((MODE == 0 || MODE == 3) && (N) == 14) dma16(sc_dst, svoff, sc_src);                 \
-        if (MODE != 2 && (N) == 13) __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0): see below */ \
+        if (MODE != 2 && (N) == 13) __builtin_amdgcn_s_waitcnt(FMT ? 0xC07F : 0xC37F); /* lgkmcnt(0 / 3): see below */ \
         if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, IC<((N) >> 1)>{});                    \
         if (MODE == 1 && !((N) & 1) && (N) < 8) issue_scales(nxt, 0, (N) >> 1, par_nxt);         \
         if (MODE == 2 && (N) == 1) issue_scales(nxt, 1, 0, par_nxt);                             \
@@ -436,7 +444,8 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         MXFP4_16(MXFP4_K3)
 #undef MXFP4_K3
         // (the scale bytes were fetched in the first half of K-step 3 and have long landed: the explicit wait
-        // in slot 13 tells the compiler so, which otherwise puts a counter wait in front of every permute)
+        // in slot 13 -- for everything but the E2M1 schedule's three younger fragment reads -- tells the compiler
+        // so, which otherwise puts a counter wait in front of every permute)
         if (MODE != 2) permute_scales();
     };
     using mode_main = std::integral_constant<int, 0>;

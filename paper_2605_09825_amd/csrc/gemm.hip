@@ -179,15 +179,19 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const ui
                  : "memory");
 }
 
-// The same to LDS[lds_base + IMM + 16*lane]: the destination sum is formed straight into M0 (one scalar
-// instruction per load: with one wave per SIMD every instruction issued between two matrix instructions
-// beyond the seven that fit under one costs matrix-unit time).
-template <int IMM>
-__device__ __forceinline__ void dma16_at(uint32_t lds_base, uint32_t voff, const uint8_t *sbase)
+// A run of such loads under one M0: each lane's 16 bytes from sbase + voff + IMM to LDS[M0 + IMM + 16*lane] (the
+// instruction's immediate offset moves both addresses; -4096 <= IMM < 4096).  Only the first load of a run
+// (SETM0) writes M0 = lds_base.
+template <int IMM, bool SETM0>
+__device__ __forceinline__ void dma16_run(uint32_t lds_base, uint32_t voff, const uint8_t *sbase)
 {
-    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t" ::"s"(lds_base), "v"(voff), "s"(sbase),
-                 "n"(IMM)
-                 : "memory", "scc");
+    static_assert(IMM >= -4096 && IMM < 4096, "13-bit signed instruction offset");
+    if (SETM0)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3\n\t" ::"s"(lds_base),
+                     "v"(voff), "s"(sbase), "n"(IMM)
+                     : "memory");
+    else
+        asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2\n\t" ::"v"(voff), "s"(sbase), "n"(IMM) : "memory");
 }
 
 template <int V>
@@ -259,19 +263,24 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     const int drr = lane >> 3, dcc = lane & 7;
     uint32_t dvo[8];
 #pragma unroll
-    for (int g = 0; g < 8; ++g)
-        dvo[g] = (uint32_t)((8 * g + drr) * rowbytes) + (uint32_t)((dcc ^ drr ^ (g & 1)) << 4);
+    for (int g = 0; g < 8; ++g)  // (less the immediate offset (g - 4) KiB the load instruction adds back)
+        dvo[g] = (uint32_t)((8 * g + drr) * rowbytes) + (uint32_t)((dcc ^ drr ^ (g & 1)) << 4) - (uint32_t)((g - 4) * 1024);
     const uint32_t lds_wave = lds0 + (uint32_t)wave * 8192u;  // the wave's 8 x 1 KiB of each operand's stage slice
     const uint32_t svoff = (uint32_t)((lane >> 1) * nkb) + (uint32_t)((lane & 1) << 4);
 
-    // load n (0..15) of stage s of tile t for this wave: even n -> A, odd n -> B; 8-row group n/2 of
-    // the wave's 64 rows
-    auto issue_load = [&](const TileSrc &t, int s, int buf, auto nc) {
-        constexpr int n = decltype(nc)::value, g = n >> 1;
+    // load n (0..15) of stage s of tile t for this wave, in issue order: n = 0..3 A's 8-row groups 0..3,
+    // 4..7 B's groups 0..3, 8..11 A's groups 4..7, 12..15 B's groups 4..7.  The four loads of a run share one M0
+    // (the LDS address of the operand's group 4; the groups sit at immediate offsets (g - 4) KiB from it);
+    // `force` makes a load set M0 itself (where scale loads, which set their own, are issued in between).
+    auto issue_load = [&](const TileSrc &t, int s, int buf, auto nc, auto force) {
+        constexpr int n = decltype(nc)::value, op = (n >> 2) & 1, g = (n >> 3) * 4 + (n & 3);
+        constexpr bool setm0 = decltype(force)::value || (n & 3) == 0;
         const int64_t koff = (int64_t)s * (STAGE_K / 2);
-        dma16_at<((n & 1) ? OFF_B : OFF_A) + g * 1024>(lds_wave + buf * STAGE_BYTES, dvo[g],
-                                                       ((n & 1) ? t.b : t.a) + koff);
+        dma16_run<(g - 4) * 1024, setm0>(lds_wave + buf * STAGE_BYTES + (op ? OFF_B : OFF_A) + 4096, dvo[g],
+                                         (op ? t.b : t.a) + koff);
     };
+    using no_force = std::false_type;
+    using force_m0 = std::true_type;
     // Scale batch b holds the 32 scale bytes per row of stages first(b) .. first(b)+3, where
     // first(b) = min(4b, nstages-4): the last batch is pulled back so that it never reads past a
     // row's end (batches past the end of K just repeat the last one into the idle buffer).
@@ -401,8 +410,8 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #define MXFP4_K0(N)                                                                              \
         if (FMT && (N) < 8) read_one(buf, 2, 2, (N));                                            \
         if (MXFP4_FRAG_SLOT(N)) read_one(buf, 1, 1, MXFP4_FRAG_OF(N));                           \
-        if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, IC<8 + ((N) >> 1)>{});       \
-        if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, IC<8 + ((N) >> 1)>{});           \
+        if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, IC<8 + ((N) >> 1)>{}, no_force{}); \
+        if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, IC<8 + ((N) >> 1)>{}, no_force{});     \
         MXFP4_SLOT_MMA(0, N, MODE == 3) MXFP4_PIN()
         MXFP4_16(MXFP4_K0)
 #undef MXFP4_K0
@@ -434,10 +443,10 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         if (MODE != 2 && MXFP4_FRAG_SLOT(N)) read_one(buf ^ 1, 0, 0, MXFP4_FRAG_OF(N));           \
         if (FMT && MODE != 2 && (N) < 8) read_one(buf ^ 1, 1, 1, (N));                            \
         if (MODE != 2 && (N) < 8) read_scale_one(s + 1, (N), par);                                \
-        if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, IC<((N) >> 1)>{}); \
-        if ((MODE == 0 || MODE == 3) && (N) == 14) dma16(sc_dst, svoff, sc_src);                 \
+        if ((MODE == 0 || MODE == 3) && (N) == 0) dma16(sc_dst, svoff, sc_src);                  \
+        if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, IC<((N) >> 1)>{}, no_force{}); \
         if (MODE != 2 && (N) == 13) __builtin_amdgcn_s_waitcnt(FMT ? 0xC07F : 0xC37F); /* lgkmcnt(0 / 3): see below */ \
-        if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, IC<((N) >> 1)>{});                    \
+        if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, IC<((N) >> 1)>{}, force_m0{});        \
         if (MODE == 1 && !((N) & 1) && (N) < 8) issue_scales(nxt, 0, (N) >> 1, par_nxt);         \
         if (MODE == 2 && (N) == 1) issue_scales(nxt, 1, 0, par_nxt);                             \
         MXFP4_SLOT_MMA(3, N, false) MXFP4_PIN()
@@ -456,7 +465,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // ---- first tile: fill the pipeline --------------------------------------------------------
     // all of stage 0, the first 8 loads of stage 1, scale batch 0 and the first load of batch 1
     TileSrc cur = tile_src(lw);
-#define MXFP4_FILL(N) issue_load(cur, 0, 0, IC<(N)>{});
+#define MXFP4_FILL(N) issue_load(cur, 0, 0, IC<(N)>{}, no_force{});
     MXFP4_16(MXFP4_FILL)
 #undef MXFP4_FILL
 #pragma unroll
@@ -474,7 +483,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         // here); after the barrier start stage 1's first half and fetch the first fragments
         if (lloc == lw) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");  // (later tiles waited before the epilogue)
         __syncthreads();
-#define MXFP4_FILL(N) if ((N) < 8) issue_load(cur, 1, bp ^ 1, IC<((N) & 7)>{});
+#define MXFP4_FILL(N) if ((N) < 8) issue_load(cur, 1, bp ^ 1, IC<((N) & 7)>{}, no_force{});
         MXFP4_16(MXFP4_FILL)
 #undef MXFP4_FILL
 #pragma unroll

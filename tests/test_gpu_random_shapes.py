@@ -48,9 +48,19 @@ def test_quantisers_on_random_shapes(kind):
         else:  # a view with a leading dimension and an offset
             base = synth.normal(rows + 32, cols + 64, scale, it, synth.STREAM_W)
             view, view_gpu = base[32:, 64:], base.to(DEV)[32:, 64:]
+            vb = synth.as_u16(view.contiguous())
             for axis in (mx.AXIS_LAST, mx.AXIS_FIRST):
                 got = mx.mxfp4_quantize(view_gpu, axis, had, rnd, seed)
-                assert same(got, oracle.quantize(synth.as_u16(view.contiguous()), axis, had, rnd, seed)), tag
+                assert same(got, oracle.quantize(vb, axis, had, rnd, seed)), tag
+                got = mx.mxfp4_quantize_fp8(view_gpu, axis, had, seed)
+                assert same(got, oracle.quantize_fp8(vb, axis, had, seed)), tag + " (fp8)"
+            got = mx.mxfp4_quantize_dual(view_gpu, had, rnd, seed)
+            want = oracle.quantize(vb, mx.AXIS_LAST, had, rnd, seed) + oracle.quantize(vb, mx.AXIS_FIRST, had, rnd, seed)
+            assert same(got, want), tag + " (dual)"
+            got = mx.mxfp4_quantize_2d(view_gpu, had, rnd, seed)
+            want = (oracle.quantize_2d(vb, mx.AXIS_LAST, had, rnd, seed) +
+                    oracle.quantize_2d(vb, mx.AXIS_FIRST, had, rnd, seed))
+            assert same(got, want), tag + " (2d)"
 
 
 @pytest.mark.parametrize("kind", ["tiles", "ragged", "small"])

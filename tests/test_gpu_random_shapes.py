@@ -95,3 +95,40 @@ def test_gemms_on_random_shapes(kind):
         tol = 1e-5 if fa == fb == mx.FMT_E2M1 else FP8_RTOL
         assert (err <= tol * absum).all(), (f"{kind} #{it}: {Ra}x{Rb}x{C} formats {fa}{fb}: "
                                             f"max err/sum|a||b| {np.max(err / np.maximum(absum, 1e-300)):.3e}")
+
+
+def test_linear_calls_on_random_recipes():
+    # random shapes, rotation, rounding, seed, geometry, stage formats and output dtypes: the training pair must
+    # reproduce the plain forward / backward calls bit for bit (Fig. 3: same three GEMMs), and all-MXFP4 recipes
+    # must match the oracle within the GEMM bound (App. C.1-C.3)
+    rng = np.random.default_rng(300)
+    for it in range(24):
+        M, N, K = (int(rng.integers(1, 12)) * 32 for _ in range(3))
+        if it % 8 == 0:
+            M, N, K = 512, 256, 1024  # whole tiles: the tiled GEMM and the side-by-side backward launch
+        had, rnd, seed = int(rng.integers(0, 4)), int(rng.integers(0, 2)), int(rng.integers(0, 2 ** 40))
+        geom = int(rng.integers(0, 2))
+        fm = [int(rng.integers(0, 2)) for _ in range(3)] if geom == mx.GEOM_1D and it % 2 else [0, 0, 0]
+        ydt, dxdt = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        cfg = mx.make_cfg(had, rnd, seed, y_dtype=ydt, dx_dtype=dxdt, dw_dtype=mx.OUT_FP32, geometry=geom,
+                          fprop_format=fm[0], dgrad_format=fm[1], wgrad_format=fm[2])
+        tag = f"#{it}: M {M} N {N} K {K} had {had} rnd {rnd} geometry {geom} formats {fm} y {ydt} dx {dxdt}"
+        x = synth.normal(M, K, 1.0, it, synth.STREAM_X)
+        w = synth.normal(N, K, 0.02, it, synth.STREAM_W)
+        dy = synth.normal(M, N, 1e-3, it, synth.STREAM_DY)
+        xg, wg, dyg = x.to(DEV), w.to(DEV), dy.to(DEV)
+        y0, _ = mx.mxfp4_linear_fwd(xg, wg, cfg)
+        dx0, dw0, _ = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg)
+        y1, _, saved = mx.mxfp4_linear_fwd_save(xg, wg, cfg)
+        dx1, dw1, _ = mx.mxfp4_linear_bwd_saved(dyg, saved, K, cfg)
+        torch.cuda.synchronize()
+        assert torch.equal(y0, y1) and torch.equal(dx0, dx1) and torch.equal(dw0, dw1), tag
+        if fm != [0, 0, 0]:
+            continue
+        xb, wb, dyb = synth.as_u16(x), synth.as_u16(w), synth.as_u16(dy)
+        yo, ya = oracle.linear_fwd(xb, wb, had, rnd, seed, geom)
+        (dxo, dxa), (dwo, dwa) = oracle.linear_bwd(dyb, xb, wb, had, rnd, seed, geom)
+        for got, want, absum, bf16 in ((y0, yo, ya, ydt == mx.OUT_BF16), (dx0, dxo, dxa, dxdt == mx.OUT_BF16),
+                                       (dw0, dwo, dwa, False)):
+            err = np.abs(got.float().cpu().numpy().astype(np.float64) - want)
+            assert (err <= 1e-5 * absum + (2.0 ** -8 * np.abs(want) if bf16 else 0.0)).all(), tag

@@ -191,6 +191,24 @@ int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N
                      const mxfp4_linear_cfg *cfg, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * mxfp4_linear_fwd for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the quantised
+ * operands are staged in a device array of MXFP4_STATIC_SCRATCH_BYTES that is part of the library's
+ * code object (every GPU the library runs on holds it until the process ends) instead of a caller's
+ * workspace.  The call allocates and frees nothing.  Same arguments, checks, kernels and results
+ * (bit for bit) as mxfp4_linear_fwd.
+ *   Limit: mxfp4_linear_workspace_bytes(M,N,K,cfg,0) <= MXFP4_STATIC_SCRATCH_BYTES, else
+ *   MXFP4_EWORKSPACE (32 MiB holds the 8B model's fused QKV forward, M=8192 K=4096 N=6144).
+ *   The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
+ *   outside any graph capture.  All calls on one GPU share the one array: two calls that overlap
+ *   in time on different streams of the same GPU race, and the array keeps the last call's operands
+ *   (nothing in it needs clearing: every byte a GEMM reads is written by that call's quantisers first).
+ */
+#define MXFP4_STATIC_SCRATCH_BYTES (32u << 20)
+int mxfp4_linear_fwd_static(const void *x, const void *w, void *y, int64_t M, int64_t N, int64_t K,
+                            const mxfp4_linear_cfg *cfg, void *hip_stream);
+
+/*
  * Backward of one linear layer: Dgrad (App. C.2) dX[M][K] = Q(dY H) Q(W^T H)^T, contraction
  * over N, and Wgrad (App. C.3) dW[N][K] = Q(dY^T H) Q(X^T H)^T, contraction over tokens M.
  *   dy bf16 [M][N], x bf16 [M][K], w bf16 [N][K], all dense.

@@ -24,7 +24,7 @@ GEOM_1D, GEOM_2D = 0, 1
 FMT_E2M1, FMT_E4M3 = 0, 1
 
 EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_quantize_fp8", "mxfp4_gemm",
-           "mxfp4_gemm_fmt", "mxfp4_linear_fwd", "mxfp4_linear_bwd",
+           "mxfp4_gemm_fmt", "mxfp4_linear_fwd", "mxfp4_linear_fwd_static", "mxfp4_linear_bwd",
            "mxfp4_linear_fwd_save", "mxfp4_linear_bwd_saved", "mxfp4_linear_saved_bytes",
            "mxfp4_linear_saved_layout", "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout",
            "mxfp4_status_string")
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
         L.mxfp4_linear_fwd.restype = ci
         L.mxfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
+        L.mxfp4_linear_fwd_static.restype = ci
+        L.mxfp4_linear_fwd_static.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp]
         L.mxfp4_linear_bwd.restype = ci
         L.mxfp4_linear_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
         L.mxfp4_linear_workspace_bytes.restype = sz
@@ -244,6 +246,20 @@ def mxfp4_linear_fwd(x, w, cfg: LinearCfg, y=None, workspace=None, stream=None):
     _check("mxfp4_linear_fwd", lib().mxfp4_linear_fwd(_ptr(x), _ptr(w), _ptr(y), M, N, K, ctypes.byref(cfg),
                                                       _ptr(workspace), workspace.numel(), _stream_ptr(stream)))
     return y, workspace
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def mxfp4_linear_fwd_static(x, w, cfg: LinearCfg, y, stream=None):
+    """mxfp4_linear_fwd on the library's own static device scratch: no workspace, nothing allocated (y is the
+    caller's).  Returns y."""
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and x.is_contiguous() and w.is_contiguous() and y.is_contiguous()
+    _check("mxfp4_linear_fwd_static", lib().mxfp4_linear_fwd_static(_ptr(x), _ptr(w), _ptr(y), M, N, K,
+                                                                    ctypes.byref(cfg), _stream_ptr(stream)))
+    return y
 
 
 def mxfp4_linear_bwd(dy, x, w, cfg: LinearCfg, dx=None, dw=None, need_dx: bool = True, need_dw: bool = True,

@@ -2,6 +2,8 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/mxfp4.h"
 #include "mxfp4_internal.h"
 
@@ -413,6 +415,48 @@ int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N
     if (rc != MXFP4_OK) return rc;
     return mxfp4_gemm_fmt(ws + L.xq, ws + L.xs, F.fprop, ws + L.wq, ws + L.ws, F.fprop, M, N, K, y, N, cfg->y_dtype, 0,
                           hip_stream);
+}
+
+// ---- forward call on the library's own scratch (for callers that cannot allocate) -----------------------
+// The quantised operands of the forward call are staged in this array instead of a caller's workspace.
+// In host code the array's name is only a stand-in for the symbol: its device address is asked for once per
+// device (each GPU holds its own copy) and only that address is ever handed to kernels.
+static __device__ __align__(256) uint8_t scratch[MXFP4_STATIC_SCRATCH_BYTES];
+
+static void *static_scratch_ptr()
+{
+    static std::mutex mu;
+    static void *ptr[64];  // per device, null until asked
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();  // (leave no sticky error behind for the caller's next HIP call)
+            return nullptr;
+        }
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
+
+int mxfp4_linear_fwd_static(const void *x, const void *w, void *y, int64_t M, int64_t N, int64_t K,
+                            const mxfp4_linear_cfg *cfg, void *hip_stream)
+{
+    int rc = check_cfg(cfg);
+    if (rc != MXFP4_OK) return rc;
+    if (M <= 0 || N <= 0 || K <= 0 || (K % 32) != 0) return MXFP4_ESHAPE;
+    // (each dimension is bounded on its own first, so that the byte count below cannot overflow)
+    if (M > (int64_t)MXFP4_STATIC_SCRATCH_BYTES || N > (int64_t)MXFP4_STATIC_SCRATCH_BYTES ||
+        K > (int64_t)MXFP4_STATIC_SCRATCH_BYTES)
+        return MXFP4_EWORKSPACE;
+    if (fwd_layout(M, N, K, stage_formats(cfg)).total > (size_t)MXFP4_STATIC_SCRATCH_BYTES) return MXFP4_EWORKSPACE;
+    if (!x || !w || !y) return MXFP4_EINVAL;  // (before the device is touched: argument errors need no GPU)
+    if (!device_ok()) return MXFP4_EDEVICE;
+    void *ws = static_scratch_ptr();
+    if (!ws) return MXFP4_EDEVICE;
+    return mxfp4_linear_fwd(x, w, y, M, N, K, cfg, ws, (size_t)MXFP4_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw, int64_t M, int64_t N,

@@ -75,17 +75,68 @@ def test_ragged_rows_and_columns_around_whole_tiles(shape):
     assert torch.equal(b16.cpu(), first.to(torch.bfloat16))
 
 
-def test_wide_scale_range_and_exactness_on_small_sums():
-    # one block per row (C = 32): at most 32 products, partial sums < 2^24 in units of the
-    # smallest product: the fp32 result must be exact
-    # (scale bytes chosen so that every result stays inside fp32's normal range)
+def as_f32(want):
+    """The oracle's fp64 value as the fp32 the kernel must deliver when the sum itself is exact: round to nearest
+    even, gradual underflow, overflow to infinity."""
+    with np.errstate(over="ignore"):
+        return want.astype(np.float32)
+
+
+@pytest.mark.parametrize("shape", [(64, 48, 32), (256, 256, 1024)])
+def test_wide_scale_range_and_exactness_on_small_sums(shape):
+    # one live block per row: at most 32 products, partial sums < 2^24 in units of the smallest product, so the
+    # fp32 result must be exact -- also where it is a subnormal number (the matrix unit does not flush them) or
+    # overflows (to infinity).  Scale bytes 60..200 put results between 2^-136 and beyond 2^128.
+    Ra, Rb, C = shape
     rng = np.random.default_rng(1)
-    aq, as_ = rand_operand(rng, 64, 32, 80, 175)
-    bq, bs = rand_operand(rng, 48, 32, 80, 175)
+    aq, as_ = rand_operand(rng, Ra, C, 60, 200)
+    bq, bs = rand_operand(rng, Rb, C, 60, 190)
+    aq[:, 16:] = 0  # (longer rows: every block but the first holds zero codes)
     want, _ = oracle.gemm(aq, as_, bq, bs)
+    w32 = as_f32(want)
+    tiny = float(np.finfo(np.float32).tiny)
+    assert ((np.abs(want) < tiny) & (want != 0)).sum() > 0 and np.isinf(w32).sum() > 0  # both regimes are present
     got = run_gemm(aq, as_, bq, bs, out_dtype=mx.OUT_FP32).cpu().numpy()
-    bad = np.argwhere(got.astype(np.float64) != want)
+    bad = np.argwhere(got != w32)
     assert bad.size == 0, (len(bad), bad[0], got[tuple(bad[0])], want[tuple(bad[0])])
+
+
+def test_results_in_the_subnormal_range_are_not_flushed():
+    # scale bytes 54..65 on both sides: every result is a multiple of 2^-148 (so fp32 holds it exactly), three in
+    # four of them below fp32's smallest normal number
+    rng = np.random.default_rng(4)
+    aq, as_ = rand_operand(rng, 96, 32, 54, 66)
+    bq, bs = rand_operand(rng, 80, 32, 54, 66)
+    want, _ = oracle.gemm(aq, as_, bq, bs)
+    tiny = float(np.finfo(np.float32).tiny)
+    assert ((np.abs(want) < tiny) & (want != 0)).mean() > 0.5
+    got = run_gemm(aq, as_, bq, bs, out_dtype=mx.OUT_FP32).cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("shape", [(64, 48, 96), (512, 256, 1024)])  # any-shape kernel, tiled kernel
+@pytest.mark.parametrize("out_dtype", [mx.OUT_FP32, mx.OUT_BF16])
+def test_scale_byte_ff_gives_nan(shape, out_dtype):
+    # 0xFF is the NaN of the E8M0 scale format (the quantiser writes it for a block that held a NaN or an
+    # infinity, with all codes 0): every output whose row of A or row of B contains such a block is NaN, whatever
+    # the codes under it, and nothing else is
+    Ra, Rb, C = shape
+    rng = np.random.default_rng(8)
+    aq, as_ = rand_operand(rng, Ra, C)
+    bq, bs = rand_operand(rng, Rb, C)
+    as_[3, 0] = 0xFF                       # live codes under the NaN scale
+    as_[Ra - 2, C // 32 - 1] = 0xFF
+    aq[Ra - 2, -16:] = 0                   # zero codes under it, as the quantiser leaves them
+    bs[7, 1] = 0xFF
+    want, absum = oracle.gemm(aq, as_, bq, bs)
+    nan_want = np.isnan(want)
+    assert nan_want[3].all() and nan_want[Ra - 2].all() and nan_want[:, 7].all()
+    assert nan_want.sum() == 2 * Rb + Ra - 2
+    got = run_gemm(aq, as_, bq, bs, out_dtype=out_dtype).float().cpu().numpy()
+    assert np.array_equal(np.isnan(got), nan_want)
+    ok = ~nan_want
+    tol = 1e-5 * absum[ok] + (2.0 ** -8 * np.abs(want[ok]) if out_dtype == mx.OUT_BF16 else 0.0)
+    assert (np.abs(got[ok] - want[ok]) <= tol).all()
 
 
 def test_bf16_output_is_rne_of_the_fp32_output():
@@ -146,50 +197,74 @@ def test_quantised_real_operands_config1():
     assert_close(y.cpu().numpy(), want, absum)
 
 
-def sample_positions(rng, Ra, Rb, n_rows=4, n_cols=4, n_tiles=24):
-    ii, jj = [], []
-    for r in list(rng.integers(0, Ra, n_rows)) + [0, Ra - 1]:
-        ii += [r] * Rb
-        jj += list(range(Rb))
-    for c in list(rng.integers(0, Rb, n_cols)) + [0, Rb - 1]:
-        ii += list(range(Ra))
-        jj += [c] * Ra
-    for _ in range(n_tiles):
-        r0, c0 = rng.integers(0, Ra - 15), rng.integers(0, Rb - 15)
-        g = np.mgrid[0:16, 0:16]
-        ii += list((r0 + g[0]).ravel())
-        jj += list((c0 + g[1]).ravel())
-    return np.array(ii, dtype=np.int64), np.array(jj, dtype=np.int64)
+def take_rows(op, rows):
+    q, s_ = op
+    return np.ascontiguousarray(q[rows]), np.ascontiguousarray(s_[rows])
+
+
+def structured_check(out, a, b, rng, fmts=(0, 0), n_lines=64, tile=256, patch=16, close=None):
+    """Parity of a large GEMM output `out` (numpy [Ra][Rb]) = A B^T on complete K-sums the oracle can afford:
+    a patch x patch block at a random place inside EVERY tile x tile output tile (one random row offset per tile
+    row, one random column offset per tile column: the patches are the cross product, one oracle GEMM), n_lines
+    whole rows and n_lines whole columns (first and last included).  a, b: (q, s) of the operands."""
+    close = close or assert_close
+    Ra, Rb = out.shape
+
+    def offsets(R):
+        idx = []
+        for t0 in range(0, R, tile):
+            span = min(tile, R - t0)
+            o = t0 + int(rng.integers(0, max(span - patch, 0) + 1))
+            idx += list(range(o, min(o + patch, R)))
+        return np.array(idx, dtype=np.int64)
+
+    def gemm(x, y):
+        return oracle.gemm_fmt(x[0], x[1], fmts[0], y[0], y[1], fmts[1])
+
+    pr, pc = offsets(Ra), offsets(Rb)
+    want, absum = gemm(take_rows(a, pr), take_rows(b, pc))
+    close(out[np.ix_(pr, pc)], want, absum)
+    rows = np.unique(np.concatenate([rng.integers(0, Ra, n_lines - 2), [0, Ra - 1]]))
+    want, absum = gemm(take_rows(a, rows), b)
+    close(out[rows], want, absum)
+    cols = np.unique(np.concatenate([rng.integers(0, Rb, n_lines - 2), [0, Rb - 1]]))
+    want, absum = gemm(a, take_rows(b, cols))
+    close(out[:, cols], want, absum)
+
+
+def close_bf16(got, want, absum):
+    assert (np.abs(got - want) <= 1e-5 * absum + 2.0**-8 * np.abs(want)).all()
 
 
 @pytest.mark.parametrize("C", [1024, 1280, 2304])
-@pytest.mark.parametrize("out_dtype", [mx.OUT_FP32, mx.OUT_BF16])
-def test_many_tiles_per_workgroup_sampled(out_dtype, C):
-    # 17 x 17 = 289 tiles of 256 x 256 (more than one per CU, not a multiple of 8); 4, 5 and 9 K-stages of 256
-    # (with an odd count the stage buffers swap roles from one tile of a workgroup to the next)
+def test_many_tiles_per_workgroup_whole_output(C):
+    # 17 x 17 = 289 tiles of 256 x 256 (more than one per CU, not a multiple of 8): tiles hand over inside a
+    # workgroup; 4, 5 and 9 K-stages of 256 (with an odd count the stage buffers swap roles from one tile of a
+    # workgroup to the next).  Every element of the output is compared, fp32 and bf16.
     Ra = Rb = 256 * 17
     rng = np.random.default_rng(5)
     aq, as_ = rand_operand(rng, Ra, C)
     bq, bs = rand_operand(rng, Rb, C)
-    out = run_gemm(aq, as_, bq, bs, out_dtype=out_dtype)
-    ii, jj = sample_positions(rng, Ra, Rb, n_rows=3, n_cols=3, n_tiles=64)
-    want, absum = oracle.gemm_at(aq, as_, bq, bs, ii, jj)
-    got = out.float().cpu().numpy()[ii, jj]
-    if out_dtype == mx.OUT_FP32:
-        assert_close(got, want, absum)
-    else:
-        assert (np.abs(got - want) <= 1e-5 * absum + 2.0**-8 * np.abs(want)).all()
+    want, absum = oracle.gemm(aq, as_, bq, bs)
+    ga, gas, gb, gbs = gpu(aq), gpu(as_), gpu(bq), gpu(bs)
+    f32 = mx.mxfp4_gemm(ga, gas, gb, gbs, out_dtype=mx.OUT_FP32)
+    b16 = mx.mxfp4_gemm(ga, gas, gb, gbs, out_dtype=mx.OUT_BF16)
+    acc = f32.clone()
+    mx.mxfp4_gemm(ga, gas, gb, gbs, out=acc, out_dtype=mx.OUT_FP32, accumulate=True)
+    torch.cuda.synchronize()
+    assert_close(f32.cpu().numpy(), want, absum)
+    assert torch.equal(b16, f32.to(torch.bfloat16))   # bf16 output = RNE of the fp32 output, everywhere
+    assert torch.equal(acc, f32 + f32)                # the accumulating epilogue, everywhere
 
 
-def test_config2_shape_sampled():
-    # 8192 x 6144 x 4096 (fused QKV Fprop): complete K-sums at whole rows, whole columns and tiles
+def test_config2_shape_every_tile():
+    # 8192 x 6144 x 4096 (fused QKV Fprop) through the two single-operation calls: complete K-sums at a patch
+    # inside every output tile, whole rows and whole columns (tests/test_gpu_configs.py compares the whole output)
     x = synth.normal(8192, 4096, 1.0, 0, synth.STREAM_X)
     w = synth.normal(6144, 4096, 0.02, 0, synth.STREAM_W)
     xq, xs = mx.mxfp4_quantize(x.to("cuda:0"), hadamard=mx.HAD_DET)
     wq, ws = mx.mxfp4_quantize(w.to("cuda:0"), hadamard=mx.HAD_DET)
     y = mx.mxfp4_gemm(xq, xs, wq, ws, out_dtype=mx.OUT_FP32)
     torch.cuda.synchronize()
-    ii, jj = sample_positions(np.random.default_rng(0), 8192, 6144)
-    want, absum = oracle.gemm_at(xq.cpu().numpy(), xs.cpu().numpy(), wq.cpu().numpy(), ws.cpu().numpy(), ii, jj)
-    got = y.cpu().numpy()[ii, jj]
-    assert_close(got, want, absum)
+    structured_check(y.cpu().numpy(), (xq.cpu().numpy(), xs.cpu().numpy()), (wq.cpu().numpy(), ws.cpu().numpy()),
+                     np.random.default_rng(0))

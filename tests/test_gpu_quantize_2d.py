@@ -9,7 +9,7 @@ import oracle
 import paper_2605_09825_amd as mx
 from paper_2605_09825_amd import synth
 from gpu_util import first_mismatch
-from test_gpu_gemm import assert_close, sample_positions
+from test_gpu_gemm import assert_close, structured_check
 from test_gpu_linear import ws_slices
 from test_gpu_dual import saved_slices
 
@@ -119,9 +119,7 @@ def run_linear_2d(x, w, dy, had, rnd, seed, full, saved_path):
     else:
         rng = np.random.default_rng(13)
         for out, ((aq, as_), (bq, bs)) in ((y, ops_f), (dx, ops_d), (dw, ops_w)):
-            ii, jj = sample_positions(rng, out.shape[0], out.shape[1], n_rows=1, n_cols=1, n_tiles=12)
-            o, absum = oracle.gemm_at(aq, as_, bq, bs, ii, jj)
-            assert_close(out.cpu().numpy()[ii, jj], o, absum)
+            structured_check(out.cpu().numpy(), (aq, as_), (bq, bs), rng)
 
 
 @pytest.mark.parametrize("saved_path", [False, True])

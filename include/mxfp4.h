@@ -86,7 +86,10 @@ typedef enum {
 typedef struct {
     int32_t hadamard;      /* mxfp4_hadamard, used for both operands of every GEMM             */
     int32_t rounding;      /* mxfp4_round                                                       */
-    uint64_t seed;         /* random-sign diagonal and stochastic-rounding counters             */
+    uint64_t seed;         /* random-sign diagonal (low 48 bits) and stochastic-rounding counters: the six
+                              quantised operands X, W, dY, W^T, dY^T, X^T of a layer round under the seeds
+                              seed ^ (k << 48), k = 0..5 in that order, so that the two operands of every
+                              GEMM draw independent variates while sharing the diagonal                  */
     int32_t y_dtype;       /* mxfp4_out for Y                                                   */
     int32_t dx_dtype;      /* mxfp4_out for dX                                                  */
     int32_t dw_dtype;      /* mxfp4_out for dW                                                  */
@@ -105,8 +108,13 @@ typedef struct {
  *            MXFP4_AXIS_FIRST: R = cols, C = rows, rows % 32 == 0, cols % 2 == 0;
  *                              x 4-byte aligned, ld % 2 == 0; q/s hold the quantised transpose
  *   q_out    uint8 [R][C/2], 16-byte aligned      s_out  uint8 [R][C/32]
- *   seed     used by MXFP4_HAD_RANDSIGN and MXFP4_SR only.  Both operands of a GEMM must
- *            use the same seed and mode for the rotation to cancel in the product.
+ *   seed     used by MXFP4_HAD_RANDSIGN and MXFP4_SR only.  Its low 48 bits (the base seed)
+ *            determine the random-sign diagonal; all 64 bits key the stochastic-rounding
+ *            counters.  Both operands of a GEMM must use the same base seed and mode for the
+ *            rotation to cancel in the product, and should differ in the high 16 bits
+ *            (MXFP4_SEED_STREAM) when rounding stochastically: the counters of A[i][c] and
+ *            B[i][c] coincide, so under one stream both would round the same way and the
+ *            diagonal of the product would be biased.
  * Per block: widen to fp32; optional sign flips; fp32 butterflies in the order
  * h = 1,2,4,8,16 then one multiply by fl32(2^-2.5) (H16: h = 1..8, multiply by 1/4);
  * scale byte = clamp(biased exponent of the block maximum - 2, 0, 254); codes = FP4 cast of
@@ -114,6 +122,8 @@ typedef struct {
  * counter hash r of (seed, row_of_q * C + column_of_q) and rounds up when u < fraction.
  * rows == 0 or cols == 0 is a valid empty call.
  */
+#define MXFP4_SEED_STREAM(base_seed, stream) \
+    (((uint64_t)(base_seed) & 0xFFFFFFFFFFFFull) | ((uint64_t)((stream) & 0xFFFF) << 48))
 int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int axis, int hadamard,
                    int rounding, uint64_t seed, void *q_out, void *s_out, void *hip_stream);
 
@@ -126,6 +136,7 @@ int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
  *            writes for MXFP4_AXIS_LAST with the same hadamard, rounding and seed
  *   q_first  uint8 [cols][rows/2], s_first uint8 [cols][rows/32]: the same for MXFP4_AXIS_FIRST
  *   q_last, q_first 16-byte aligned.  rows == 0 or cols == 0 is a valid empty call.
+ *   Both outputs round under the one seed given (they are operands of different GEMMs).
  */
 int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
                         int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
@@ -171,10 +182,15 @@ int mxfp4_gemm_fmt(const void *a_q, const void *a_s, int a_format, const void *b
  * Block-scaled FP4 GEMM on quantised operands (the MXFP4 GEMM that replaces the FP8 GEMM of
  * the linear layers, Sec. 1 and App. A.2):
  *     out[i][j] (+)= sum_c A[i][c] * B[j][c],  A = a_q/a_s [R_a][C],  B = b_q/b_s [R_b][C]
- * products exact, fp32 accumulation.  C % 32 == 0; R_a, R_b >= 0 (0 = empty call).
+ * products exact, fp32 accumulation (partial sums of 64 or 128 consecutive elements are formed
+ * exactly enough to meet 1e-5 * sum|a||b| against the exact sum and are added in fp32, round to
+ * nearest even, with gradual underflow: results below 2^-126 come out as fp32 subnormal numbers,
+ * not flushed; results beyond fp32's range come out as infinities).  C % 32 == 0; R_a, R_b >= 0
+ * (0 = empty call).
  *   out        [R_a][ld_out] bf16 or fp32 (out_dtype), ld_out >= R_b
  *   accumulate 1: out += result (MXFP4_OUT_FP32 only), 0: out = result
- * All operand pointers 16-byte aligned.  A scale byte of 0xFF yields NaN outputs.
+ * All operand pointers 16-byte aligned.  A scale byte of 0xFF (the NaN of the scale format) makes
+ * every output of that operand row NaN, whatever the codes under it.
  */
 int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_s, int64_t R_a, int64_t R_b,
                int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream);

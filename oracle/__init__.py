@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.orc_rand32_array.argtypes = [ctypes.c_uint64, ctypes.c_uint64, i64, ctypes.POINTER(ctypes.c_uint32)]
         L.orc_sign_mask.restype = ctypes.c_uint32
         L.orc_sign_mask.argtypes = [ctypes.c_uint64]
+        L.orc_seed_with_stream.restype = ctypes.c_uint64
+        L.orc_seed_with_stream.argtypes = [ctypes.c_uint64, ctypes.c_uint]
         L.orc_bf16_to_f32.restype = ctypes.c_float
         L.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
         L.orc_e2m1_decode.restype = ctypes.c_double
@@ -320,9 +322,19 @@ def _q(geom):
     return quantize_2d if geom == GEOM_2D else quantize
 
 
+# Rounding stream of each of the six quantised operands of a linear layer (high 16 bits of the seed): the two
+# operands of every GEMM round under different streams, the random-sign diagonal (low 48 bits) is shared.
+STREAM_X, STREAM_W, STREAM_DY, STREAM_WT, STREAM_DYT, STREAM_XT = range(6)
+
+
+def seed_with_stream(seed: int, stream: int) -> int:
+    return int(lib().orc_seed_with_stream(seed & (2**64 - 1), stream))
+
+
 def linear_fwd_operands(x, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
     """Fprop Y = X W^T: both operands rotated/quantised along K (App. C.1)."""
-    return _q(geom)(x, AXIS_LAST, had, rnd, seed), _q(geom)(w, AXIS_LAST, had, rnd, seed)
+    return (_q(geom)(x, AXIS_LAST, had, rnd, seed_with_stream(seed, STREAM_X)),
+            _q(geom)(w, AXIS_LAST, had, rnd, seed_with_stream(seed, STREAM_W)))
 
 
 def linear_fwd(x, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
@@ -333,13 +345,15 @@ def linear_fwd(x, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
 def linear_dgrad_operands(dy, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
     """Dgrad dX = dY W: contraction over N; dY[M,N] along its last axis, W[N,K]
     along its first axis (giving W^T rows) (App. C.2)."""
-    return _q(geom)(dy, AXIS_LAST, had, rnd, seed), _q(geom)(w, AXIS_FIRST, had, rnd, seed)
+    return (_q(geom)(dy, AXIS_LAST, had, rnd, seed_with_stream(seed, STREAM_DY)),
+            _q(geom)(w, AXIS_FIRST, had, rnd, seed_with_stream(seed, STREAM_WT)))
 
 
 def linear_wgrad_operands(dy, x, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):
     """Wgrad dW = dY^T X: contraction over tokens M; both operands quantised down
     their first axis (App. C.3)."""
-    return _q(geom)(dy, AXIS_FIRST, had, rnd, seed), _q(geom)(x, AXIS_FIRST, had, rnd, seed)
+    return (_q(geom)(dy, AXIS_FIRST, had, rnd, seed_with_stream(seed, STREAM_DYT)),
+            _q(geom)(x, AXIS_FIRST, had, rnd, seed_with_stream(seed, STREAM_XT)))
 
 
 def linear_bwd(dy, x, w, had=HAD_NONE, rnd=RNE, seed=0, geom=GEOM_1D):

@@ -75,11 +75,26 @@ void orc_rand32_array(uint64_t seed, uint64_t idx0, int64_t n, uint32_t *out)
     for (int64_t k = 0; k < n; ++k) out[k] = orc_rand32(seed, idx0 + (uint64_t)k);
 }
 
+/* A 64-bit seed has two parts.  The low 48 bits are the base seed: the random-sign
+ * diagonal depends on them alone, so that both operands of a GEMM, which must share
+ * the diagonal for the rotation to cancel (App. C), can still differ in the high 16
+ * bits, the stream number.  Stochastic rounding uses all 64 bits: operands rounded
+ * under different streams draw independent variates.  (With one stream for both
+ * operands of out[i][j] = sum_c A[i][c] B[j][c] the elements A[i][c] and B[i][c]
+ * would share their variate, and the product of two roundings that move together is
+ * biased: unbiasedness is the reason stochastic rounding is tried at all, Sec. 3.1.) */
+#define ORC_SEED_BASE_MASK 0xFFFFFFFFFFFFull
+
+uint64_t orc_seed_with_stream(uint64_t seed, unsigned stream)
+{
+    return seed ^ ((uint64_t)(stream & 0xFFFFu) << 48);
+}
+
 /* The +-1 diagonal of the random-sign Hadamard: bit i set means d_i = -1.
  * One mask per call, the same for every block and for both GEMM operands. */
 uint32_t orc_sign_mask(uint64_t seed)
 {
-    return orc_rand32(seed, 0xFFFFFFFFFFFFFFFFull);
+    return orc_rand32(seed & ORC_SEED_BASE_MASK, 0xFFFFFFFFFFFFFFFFull);
 }
 
 /* ------------------------------------------------------------------------- */

@@ -186,7 +186,8 @@ int mxfp4_quantize(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
 // Argument checks of the two-output calls.  Return -1 and fill `a` when a launch is due, else the status to
 // hand back (MXFP4_OK for an empty tensor).
 static int prep_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard, int rounding,
-                     uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first, QuantArgs &a)
+                     uint64_t seed_last, uint64_t seed_first, void *q_last, void *s_last, void *q_first,
+                     void *s_first, QuantArgs &a)
 {
     // the union of the two single-axis argument rules
     int rc = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_LAST, hadamard, rounding, q_last, s_last);
@@ -194,15 +195,17 @@ static int prep_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_
     if (rc > 0) return rc;
     if (rc2 > 0) return rc2;
     if (rc == 0 || rc2 == 0) return MXFP4_OK;
-    a = QuantArgs{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
+    a = QuantArgs{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed_first,
                   static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
     a.q_row = static_cast<uint8_t *>(q_last);
     a.s_row = static_cast<uint8_t *>(s_last);
+    a.seed_row = seed_last;
     return -1;
 }
 
 static int prep_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard, int rounding,
-                   uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first, QuantArgs &a)
+                   uint64_t seed_last, uint64_t seed_first, void *q_last, void *s_last, void *q_first,
+                   void *s_first, QuantArgs &a)
 {
     const bool want_last = q_last || s_last, want_first = q_first || s_first;
     if (hadamard < MXFP4_HAD_NONE || hadamard > MXFP4_HAD_DET16) return MXFP4_EINVAL;
@@ -221,35 +224,43 @@ static int prep_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
         if (rc >= 0) return rc;
     }
     if (!aligned(x_bf16, 16) || (ld_elems % 8) != 0) return MXFP4_EALIGN;
-    a = QuantArgs{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed,
+    a = QuantArgs{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, rounding, seed_first,
                   static_cast<uint8_t *>(q_first), static_cast<uint8_t *>(s_first)};
     a.q_row = static_cast<uint8_t *>(q_last);
     a.s_row = static_cast<uint8_t *>(s_last);
+    a.seed_row = seed_last;
     return -1;
+}
+
+// the two-output quantisers with a seed per output (the linear calls give every operand its own rounding stream)
+static int quantize_dual_seeds(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                               int rounding, uint64_t seed_last, uint64_t seed_first, void *q_last, void *s_last,
+                               void *q_first, void *s_first, bool geom_2d, void *hip_stream)
+{
+    QuantArgs a;
+    int rc = (geom_2d ? prep_2d : prep_dual)(x_bf16, rows, cols, ld_elems, hadamard, rounding, seed_last, seed_first,
+                                             q_last, s_last, q_first, s_first, a);
+    if (rc >= 0) return rc;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = geom_2d ? launch_quantize_2d(a, nullptr, st) : launch_quantize_dual(a, nullptr, st);
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
 int mxfp4_quantize_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
                         int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
                         void *hip_stream)
 {
-    QuantArgs a;
-    int rc = prep_dual(x_bf16, rows, cols, ld_elems, hadamard, rounding, seed, q_last, s_last, q_first, s_first, a);
-    if (rc >= 0) return rc;
-    if (!device_ok()) return MXFP4_EDEVICE;
-    hipError_t e = launch_quantize_dual(a, nullptr, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+    return quantize_dual_seeds(x_bf16, rows, cols, ld_elems, hadamard, rounding, seed, seed, q_last, s_last, q_first,
+                               s_first, false, hip_stream);
 }
 
 int mxfp4_quantize_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
                       int rounding, uint64_t seed, void *q_last, void *s_last, void *q_first, void *s_first,
                       void *hip_stream)
 {
-    QuantArgs a;
-    int rc = prep_2d(x_bf16, rows, cols, ld_elems, hadamard, rounding, seed, q_last, s_last, q_first, s_first, a);
-    if (rc >= 0) return rc;
-    if (!device_ok()) return MXFP4_EDEVICE;
-    hipError_t e = launch_quantize_2d(a, nullptr, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+    return quantize_dual_seeds(x_bf16, rows, cols, ld_elems, hadamard, rounding, seed, seed, q_last, s_last, q_first,
+                               s_first, true, hip_stream);
 }
 
 int mxfp4_quantize_fp8(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int axis, int hadamard,
@@ -288,43 +299,49 @@ int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_
                           accumulate, hip_stream);
 }
 
+// Rounding stream of each quantised operand of a layer (the high 16 bits of its seed).  Both operands of every
+// GEMM get different streams: with a shared one, A[i][c] and B[i][c] of out[i][j] = sum_c A[i][c] B[j][c] would
+// draw the same stochastic-rounding variate and the diagonal of the product would be biased, which defeats the
+// purpose of stochastic rounding (Sec. 3.1).  The random-sign diagonal comes from the low 48 bits and stays
+// common to all six, as the cancellation of App. C requires.
+enum OperandStream { STREAM_X = 0, STREAM_W = 1, STREAM_DY = 2, STREAM_WT = 3, STREAM_DYT = 4, STREAM_XT = 5 };
+static uint64_t operand_seed(const mxfp4_linear_cfg *cfg, int stream) { return cfg->seed ^ ((uint64_t)stream << 48); }
+
 // One dense tensor of a linear layer: the row-wise output (q_last, s_last) in format fmt_last, the column-wise
-// one (q_first, s_first) in fmt_first, or both (a null pair = not wanted).  MXFP4 outputs follow the layer's
-// rotation, rounding and geometry, and come from one pass over the tensor when both are MXFP4; an MXFP8 output
-// is unrotated and rounded to nearest (the rotation and the rounding mode are stabilisers of the MXFP4 GEMMs,
-// Table 1).
+// one (q_first, s_first) in fmt_first, or both (a null pair = not wanted); st_last / st_first: their OperandStream.
+// MXFP4 outputs follow the layer's rotation, rounding and geometry, and come from one pass over the tensor when
+// both are MXFP4; an MXFP8 output is unrotated and rounded to nearest (the rotation and the rounding mode are
+// stabilisers of the MXFP4 GEMMs, Table 1).
 static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t rows, int64_t cols, int fmt_last,
-                            uint8_t *q_last, uint8_t *s_last, int fmt_first, uint8_t *q_first, uint8_t *s_first,
-                            void *hip_stream)
+                            int st_last, uint8_t *q_last, uint8_t *s_last, int fmt_first, int st_first,
+                            uint8_t *q_first, uint8_t *s_first, void *hip_stream)
 {
+    const uint64_t seed_last = operand_seed(cfg, st_last), seed_first = operand_seed(cfg, st_first);
     if (q_last && fmt_last == MXFP4_FMT_E4M3) {
-        int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_LAST, MXFP4_HAD_NONE, cfg->seed, q_last, s_last,
+        int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_LAST, MXFP4_HAD_NONE, seed_last, q_last, s_last,
                                     hip_stream);
         if (rc != MXFP4_OK) return rc;
         q_last = s_last = nullptr;
     }
     if (q_first && fmt_first == MXFP4_FMT_E4M3) {
-        int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_FIRST, MXFP4_HAD_NONE, cfg->seed, q_first,
+        int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_FIRST, MXFP4_HAD_NONE, seed_first, q_first,
                                     s_first, hip_stream);
         if (rc != MXFP4_OK) return rc;
         q_first = s_first = nullptr;
     }
     if (!q_last && !q_first) return MXFP4_OK;
-    if (cfg->geometry == MXFP4_GEOM_2D)
-        return mxfp4_quantize_2d(x, rows, cols, cols, cfg->hadamard, cfg->rounding, cfg->seed, q_last, s_last,
-                                 q_first, s_first, hip_stream);
-    if (q_last && q_first)
-        return mxfp4_quantize_dual(x, rows, cols, cols, cfg->hadamard, cfg->rounding, cfg->seed, q_last, s_last,
-                                   q_first, s_first, hip_stream);
+    if (cfg->geometry == MXFP4_GEOM_2D || (q_last && q_first))
+        return quantize_dual_seeds(x, rows, cols, cols, cfg->hadamard, cfg->rounding, seed_last, seed_first, q_last,
+                                   s_last, q_first, s_first, cfg->geometry == MXFP4_GEOM_2D, hip_stream);
     if (q_last)
-        return mxfp4_quantize(x, rows, cols, cols, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, cfg->seed, q_last,
+        return mxfp4_quantize(x, rows, cols, cols, MXFP4_AXIS_LAST, cfg->hadamard, cfg->rounding, seed_last, q_last,
                               s_last, hip_stream);
-    return mxfp4_quantize(x, rows, cols, cols, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, cfg->seed, q_first,
+    return mxfp4_quantize(x, rows, cols, cols, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, seed_first, q_first,
                           s_first, hip_stream);
 }
 
-// Both MXFP4 outputs of two dense tensors (the operands X and W of a forward call that also saves for the
-// backward call) in one launch.
+// Both MXFP4 outputs of the two dense tensors X and W of a forward call that also saves for the backward call,
+// in one launch.
 static int quantize_operand_pair(const mxfp4_linear_cfg *cfg, const void *x0, int64_t rows0, int64_t cols0,
                                  uint8_t *ql0, uint8_t *sl0, uint8_t *qf0, uint8_t *sf0, const void *x1,
                                  int64_t rows1, int64_t cols1, uint8_t *ql1, uint8_t *sl1, uint8_t *qf1,
@@ -333,9 +350,11 @@ static int quantize_operand_pair(const mxfp4_linear_cfg *cfg, const void *x0, in
     const bool g2 = cfg->geometry == MXFP4_GEOM_2D;
     QuantArgs a, b;
     auto prep = g2 ? prep_2d : prep_dual;
-    int rc = prep(x0, rows0, cols0, cols0, cfg->hadamard, cfg->rounding, cfg->seed, ql0, sl0, qf0, sf0, a);
+    int rc = prep(x0, rows0, cols0, cols0, cfg->hadamard, cfg->rounding, operand_seed(cfg, STREAM_X),
+                  operand_seed(cfg, STREAM_XT), ql0, sl0, qf0, sf0, a);
     if (rc > 0) return rc;
-    int rc1 = prep(x1, rows1, cols1, cols1, cfg->hadamard, cfg->rounding, cfg->seed, ql1, sl1, qf1, sf1, b);
+    int rc1 = prep(x1, rows1, cols1, cols1, cfg->hadamard, cfg->rounding, operand_seed(cfg, STREAM_W),
+                   operand_seed(cfg, STREAM_WT), ql1, sl1, qf1, sf1, b);
     if (rc1 > 0) return rc1;
     if (rc == 0 && rc1 == 0) return MXFP4_OK;
     if (!device_ok()) return MXFP4_EDEVICE;
@@ -409,9 +428,9 @@ int mxfp4_linear_fwd(const void *x, const void *w, void *y, int64_t M, int64_t N
     if (workspace_bytes < L.total) return MXFP4_EWORKSPACE;
     if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    rc = quantize_operand(cfg, x, M, K, F.fprop, ws + L.xq, ws + L.xs, 0, nullptr, nullptr, hip_stream);
+    rc = quantize_operand(cfg, x, M, K, F.fprop, STREAM_X, ws + L.xq, ws + L.xs, 0, 0, nullptr, nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    rc = quantize_operand(cfg, w, N, K, F.fprop, ws + L.wq, ws + L.ws, 0, nullptr, nullptr, hip_stream);
+    rc = quantize_operand(cfg, w, N, K, F.fprop, STREAM_W, ws + L.wq, ws + L.ws, 0, 0, nullptr, nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
     return mxfp4_gemm_fmt(ws + L.xq, ws + L.xs, F.fprop, ws + L.wq, ws + L.ws, F.fprop, M, N, K, y, N, cfg->y_dtype, 0,
                           hip_stream);
@@ -481,15 +500,17 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
     if ((N % 8) != 0 || (K % 8) != 0) return MXFP4_EALIGN;  // dense bf16 rows must stay 16-byte aligned
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     // dY is needed row-wise for Dgrad and column-wise for Wgrad: one pass when both are asked
-    rc = quantize_operand(cfg, dy, M, N, F.dgrad, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr, F.wgrad,
-                          dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
+    rc = quantize_operand(cfg, dy, M, N, F.dgrad, STREAM_DY, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
+                          F.wgrad, STREAM_DYT, dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
     if (dx) {
-        rc = quantize_operand(cfg, w, N, K, 0, nullptr, nullptr, F.dgrad, ws + L.wtq, ws + L.wts, hip_stream);
+        rc = quantize_operand(cfg, w, N, K, 0, 0, nullptr, nullptr, F.dgrad, STREAM_WT, ws + L.wtq, ws + L.wts,
+                              hip_stream);
         if (rc != MXFP4_OK) return rc;
     }
     if (dw) {
-        rc = quantize_operand(cfg, x, M, K, 0, nullptr, nullptr, F.wgrad, ws + L.xtq, ws + L.xts, hip_stream);
+        rc = quantize_operand(cfg, x, M, K, 0, 0, nullptr, nullptr, F.wgrad, STREAM_XT, ws + L.xtq, ws + L.xts,
+                              hip_stream);
         if (rc != MXFP4_OK) return rc;
     }
     const GemmArgs gd{ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0,
@@ -539,9 +560,11 @@ int mxfp4_linear_fwd_save(const void *x, const void *w, void *y, int64_t M, int6
                                    ws + L.ws, sv + S.wtq, sv + S.wts, hip_stream);
         if (rc != MXFP4_OK) return rc;
     } else {
-        rc = quantize_operand(cfg, x, M, K, F.fprop, ws + L.xq, ws + L.xs, F.wgrad, sv + S.xtq, sv + S.xts, hip_stream);
+        rc = quantize_operand(cfg, x, M, K, F.fprop, STREAM_X, ws + L.xq, ws + L.xs, F.wgrad, STREAM_XT, sv + S.xtq,
+                              sv + S.xts, hip_stream);
         if (rc != MXFP4_OK) return rc;
-        rc = quantize_operand(cfg, w, N, K, F.fprop, ws + L.wq, ws + L.ws, F.dgrad, sv + S.wtq, sv + S.wts, hip_stream);
+        rc = quantize_operand(cfg, w, N, K, F.fprop, STREAM_W, ws + L.wq, ws + L.ws, F.dgrad, STREAM_WT, sv + S.wtq,
+                              sv + S.wts, hip_stream);
         if (rc != MXFP4_OK) return rc;
     }
     return mxfp4_gemm_fmt(ws + L.xq, ws + L.xs, F.fprop, ws + L.wq, ws + L.ws, F.fprop, M, N, K, y, N, cfg->y_dtype, 0,
@@ -566,8 +589,8 @@ int mxfp4_linear_bwd_saved(const void *dy, const void *saved, size_t saved_bytes
         return MXFP4_EALIGN;
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const uint8_t *sv = static_cast<const uint8_t *>(saved);
-    rc = quantize_operand(cfg, dy, M, N, F.dgrad, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr, F.wgrad,
-                          dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
+    rc = quantize_operand(cfg, dy, M, N, F.dgrad, STREAM_DY, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
+                          F.wgrad, STREAM_DYT, dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
     const GemmArgs gd{ws + L.gq, ws + L.gs, sv + S.wtq, sv + S.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0,
                       F.dgrad, F.dgrad};

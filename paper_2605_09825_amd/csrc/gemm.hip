@@ -653,6 +653,20 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p
 
 }  // namespace
 
+// Compute units of the current device (MI355X: 256); asked once per process and device.
+static int device_cus()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return NUM_CUS;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = NUM_CUS;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 // the tiled kernel wants whole 256 x 256 tiles, K in whole stages (128 bytes of codes per row: 256 E2M1
 // or 128 E4M3 elements) and at least 1024 (scale bytes are fetched 32 per row), and 16-byte aligned
 // code rows and output rows
@@ -662,7 +676,7 @@ static bool tile_eligible(const GemmArgs &g)
     const bool k_ok = g.C >= 1024 && (g.C % (g.a_fmt ? 128 : 256)) == 0;
     return k_ok && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.ld % 8) == 0 &&
            (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 && (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 &&
-           (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) && g.C < (int64_t(1) << 31);
+           (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) && g.C < (int64_t(1) << 26);  // (64 code rows: 32-bit lane offsets)
 }
 
 static TileGemm tile_args(const GemmArgs &g)
@@ -700,7 +714,8 @@ static hipError_t launch_tiled_f(const GemmArgs &g, hipStream_t st)
     const TileGemm p = tile_args(g);
     // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
     const int T = p.tiles_m * p.tiles_n;
-    dim3 grid((unsigned)(T < NUM_CUS ? T : NUM_CUS));
+    const int cus = device_cus();
+    dim3 grid((unsigned)(T < cus ? T : cus));
     if (g.out_fp32) {
         if (g.accumulate)
             hipLaunchKernelGGL((gemm_tile_kernel<true, true, FMT>), grid, dim3(256), 0, st, p);
@@ -760,7 +775,9 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
 // when both fit the tiled kernel and together fill the chip; otherwise one after the other.
 hipError_t launch_gemm_pair(const GemmArgs &g0, const GemmArgs &g1, hipStream_t st)
 {
-    const bool side_by_side = !g0.accumulate && g0.a_fmt == 0 && g1.a_fmt == 0 && tile_eligible(g0) && tile_eligible(g1);
+    // (the split below counts on 8 XCDs of 32 compute units each)
+    const bool side_by_side = !g0.accumulate && g0.a_fmt == 0 && g1.a_fmt == 0 && tile_eligible(g0) &&
+                              tile_eligible(g1) && device_cus() == NUM_CUS;
     if (side_by_side) {
         const TileGemm p0 = tile_args(g0), p1 = tile_args(g1);
         const int64_t t0 = (int64_t)p0.tiles_m * p0.tiles_n, t1 = (int64_t)p1.tiles_m * p1.tiles_n;

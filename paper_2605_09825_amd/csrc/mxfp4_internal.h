@@ -13,8 +13,13 @@ struct QuantArgs {
     int hadamard, rounding;
     uint64_t seed;
     uint8_t *q, *s;
-    uint8_t *q_row = nullptr, *s_row = nullptr;  // launch_quantize_dual only: the row-wise outputs
+    uint8_t *q_row = nullptr, *s_row = nullptr;  // launch_quantize_dual / _2d only: the row-wise outputs
+    uint64_t seed_row = 0;                       // ... and the seed their stochastic rounding draws from
 };
+
+// A seed's low 48 bits (the base seed) fix the random-sign diagonal; its high 16 bits only select the stream of
+// stochastic-rounding variates, so the two operands of a GEMM can share the diagonal and still round independently.
+constexpr uint64_t SEED_BASE_MASK = 0xFFFFFFFFFFFFull;
 
 // blocks along rows (1x32): q[rows][cols/2], s[rows][cols/32]
 hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st);

@@ -57,6 +57,9 @@ RngKey make_key(uint64_t seed)
     return k;
 }
 
+// the +-1 diagonal of the random-sign rotation: a function of the base seed alone
+uint32_t sign_mask_of(uint64_t seed) { return rand32(make_key(seed & SEED_BASE_MASK), 0xFFFFFFFFFFFFFFFFull); }
+
 // ---- one block in registers ---------------------------------------------------------
 template <int N>
 __device__ __forceinline__ void butterflies(float (&v)[32])
@@ -281,11 +284,12 @@ struct TileJob {
     uint8_t *q, *s, *q_row, *s_row;
     uint32_t col_groups, nblocks, band_rows;
     int s_vec8, s_row_vec4, streaming;
+    RngKey key, key_row;  // stochastic-rounding streams of the column-wise and of the row-wise output
 };
 
 template <int HAD, int RND, int MODE>
 __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, const TileJob job1,
-                                                            uint32_t sign_mask, RngKey key)
+                                                            uint32_t sign_mask)
 {
     const bool second = blockIdx.x >= job0.nblocks;  // uniform: everything below is selected per workgroup
     const uint16_t *__restrict__ x = second ? job1.x : job0.x;
@@ -300,6 +304,7 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     const uint32_t band_rows = second ? job1.band_rows : job0.band_rows;
     const int s_vec8 = second ? job1.s_vec8 : job0.s_vec8, s_row_vec4 = second ? job1.s_row_vec4 : job0.s_row_vec4;
     const int streaming = second ? job1.streaming : job0.streaming;
+    const RngKey key = second ? job1.key : job0.key, key_row = second ? job1.key_row : job0.key_row;
     const uint32_t bid = blockIdx.x - (second ? job0.nblocks : 0u);
 
     // LDS: per wave one slice that first holds the wave's parked 32 x 128 elements (DUAL, 2D) and then its
@@ -385,7 +390,7 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
             rotated_row(pass, v);
             uint4 codes;
             uint32_t sb;
-            encode_scaled<RND>(v, MODE == MODE_2D ? region_max : amax_bits(v), key,
+            encode_scaled<RND>(v, MODE == MODE_2D ? region_max : amax_bits(v), key_row,
                                (uint64_t)row * (uint64_t)cols + (uint64_t)colb, codes, sb);
             const int64_t g = row * bpr + (colb >> 5);
             if (on) store_codes(reinterpret_cast<uint4 *>(q_row) + g, codes, streaming);
@@ -593,8 +598,7 @@ __global__ __launch_bounds__(512) void quantize_cols_fp8_kernel(const uint16_t *
 template <int HAD>
 hipError_t launch_fp8_h(const QuantArgs &a, bool cols_axis, hipStream_t st)
 {
-    const RngKey key = make_key(a.seed);
-    const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
+    const uint32_t sign_mask = sign_mask_of(a.seed);
     if (cols_axis) {
         const int64_t nrb = a.rows / 32;
         const uint32_t col_groups = (uint32_t)((a.cols + CT_COLS - 1) / CT_COLS);
@@ -616,7 +620,7 @@ hipError_t launch_rows_h(const QuantArgs &a, hipStream_t st)
     const int64_t bpr = a.cols / 32, nblocks = a.rows * bpr;
     const unsigned grid = (unsigned)((nblocks + 255) / 256);
     const RngKey key = make_key(a.seed);
-    const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
+    const uint32_t sign_mask = sign_mask_of(a.seed);
     const int dense = (a.ld == a.cols);
     const int streaming = a.rows * a.cols * 2 > LLC_BYTES;
     if (a.rounding == RND_RNE)
@@ -643,10 +647,12 @@ TileJob make_job(const QuantArgs &a)
     j.s_vec8 = ((nrb % 8) == 0) && ((reinterpret_cast<uintptr_t>(a.s) % 8) == 0);
     j.s_row_vec4 = MODE != MODE_COLS && a.s_row != nullptr && (((a.cols / 32) % 4) == 0) &&
                    ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
+    j.key = make_key(a.seed);
+    j.key_row = make_key(a.seed_row);
     return j;
 }
 
-// b == nullptr: one tensor.  Otherwise both tensors in one launch (same rotation, rounding and seed).
+// b == nullptr: one tensor.  Otherwise both tensors in one launch (same rotation, rounding and base seed).
 template <int HAD, int MODE>
 hipError_t launch_cols_h(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
 {
@@ -655,12 +661,11 @@ hipError_t launch_cols_h(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
     j1.nblocks = 0;
     if (b) j1 = make_job<MODE>(*b);
     dim3 grid(j0.nblocks + j1.nblocks);
-    const RngKey key = make_key(a.seed);
-    const uint32_t sign_mask = rand32(key, 0xFFFFFFFFFFFFFFFFull);
+    const uint32_t sign_mask = sign_mask_of(a.seed);
     if (a.rounding == RND_RNE)
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask, key);
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask);
     else
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask, key);
+        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask);
     return hipGetLastError();
 }
 

@@ -79,6 +79,33 @@ def test_bwd_skips_and_accumulates():
     assert torch.allclose(dw2, 2 * dw, rtol=1e-6, atol=0)
 
 
+def test_operands_of_a_gemm_round_under_their_own_streams_and_share_the_sign_diagonal():
+    # random-sign rotation + stochastic rounding, seed with bits in its stream field: each of the six operands
+    # must equal the single-tensor quantiser's output under seed ^ (k << 48)
+    M, N, K = 128, 160, 96
+    seed = 0xABCD_1234_5678_9ABC
+    x = synth.normal(M, K, 1.0, 3, synth.STREAM_X)
+    w = synth.normal(N, K, 0.02, 3, synth.STREAM_W)
+    dy = synth.normal(M, N, 1e-3, 3, synth.STREAM_DY)
+    cfg = mx.make_cfg(mx.HAD_RANDSIGN, mx.SR, seed, y_dtype=mx.OUT_FP32, dx_dtype=mx.OUT_FP32, dw_dtype=mx.OUT_FP32)
+    xg, wg, dyg = x.to("cuda:0"), w.to("cuda:0"), dy.to("cuda:0")
+    _, ws_f = mx.mxfp4_linear_fwd(xg, wg, cfg)
+    _, _, ws_b = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg)
+    torch.cuda.synchronize()
+    got = ws_slices(ws_f, M, N, K, False) + ws_slices(ws_b, M, N, K, True)
+    src = [(xg, mx.AXIS_LAST), (wg, mx.AXIS_LAST), (dyg, mx.AXIS_LAST), (wg, mx.AXIS_FIRST), (dyg, mx.AXIS_FIRST),
+           (xg, mx.AXIS_FIRST)]
+    cpu = {id(xg): x, id(wg): w, id(dyg): dy}
+    for k, ((t, axis), (q, s)) in enumerate(zip(src, got)):
+        sk = seed ^ (k << 48)
+        q1, s1 = mx.mxfp4_quantize(t, axis, mx.HAD_RANDSIGN, mx.SR, sk)
+        qo, so = oracle.quantize(synth.as_u16(cpu[id(t)]), axis, oracle.HAD_RANDSIGN, oracle.SR, sk)
+        assert np.array_equal(q, q1.cpu().numpy()) and np.array_equal(s, s1.cpu().numpy()), k
+        assert np.array_equal(q, qo) and np.array_equal(s, so), k
+    # (same base seed, so the same diagonal: operands 0 and 1 differ from a run with another stream only in rounding)
+    assert oracle.sign_mask(seed) == oracle.sign_mask(seed ^ (5 << 48))
+
+
 def test_config2_all_three_stages_every_tile():
     # Llama-3.1-8B fused QKV: M=8192, K=4096, N=6144, deterministic Hadamard, RNE
     M, N, K = 8192, 6144, 4096

@@ -149,3 +149,24 @@ def test_more_than_2_32_elements_stochastic_rounding_counters():
     assert np.array_equal(q, qo), "codes: " + first_mismatch(q, qo)
     # the same values at different positions round differently (the counter, not the value, decides)
     assert not np.array_equal(q[:4097], q[-4097:])
+
+
+def test_blocks_that_expose_the_rotation_rounding_order(golden_dir):
+    # the input blocks of tests/golden/rotation_sensitive_blocks.txt sit next to an FP4 rounding threshold after the
+    # rotation: a multiply placed before the butterflies, a constant one ulp off or another stage order changes
+    # their codes.  Row-wise (one block per row) and column-wise (one block per column, padded to 2 columns)
+    import os
+    rows = []
+    for line in open(os.path.join(golden_dir, "rotation_sensitive_blocks.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        rows.append([int(h, 16) for h in line.split()[1:]])
+    blocks = synth.from_bits(np.array(rows, dtype=np.uint16))        # [16][32]
+    assert blocks.shape[1] == 32 and blocks.shape[0] % 2 == 0
+    for had in (mx.HAD_DET, mx.HAD_RANDSIGN):
+        check(blocks, mx.AXIS_LAST, had, mx.RNE, seed=0 if had == mx.HAD_DET else 99)
+    check(blocks.t().contiguous(), mx.AXIS_FIRST, mx.HAD_DET, mx.RNE)
+    ql, sl, qf, sf = mx.mxfp4_quantize_dual(blocks.t().contiguous().to("cuda:0"), mx.HAD_DET)   # [32][16]: both ways
+    torch.cuda.synchronize()
+    qo, so = oracle.quantize(synth.as_u16(blocks), oracle.AXIS_LAST, oracle.HAD_DET)
+    assert np.array_equal(qf.cpu().numpy(), qo) and np.array_equal(sf.cpu().numpy(), so)

@@ -2,6 +2,7 @@
 of eq. (1), the axis conventions of App. D / App. C, and the indexing of the
 stochastic-rounding counter."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -269,3 +270,113 @@ def test_sr_brackets_and_differs_from_rne():
     # mean error over many elements ~ 0 (unbiased), unlike the magnitude of RNE's worst case
     signed_err = (np.abs(oracle.dequantize(q, s)) / 2.0**E - t)
     assert abs(signed_err.mean()) < 4 * signed_err.std() / math.sqrt(signed_err.size)
+
+
+# ------------------------------------------------------------ rounding streams (high 16 bits of the seed)
+def test_streams_share_the_sign_diagonal_and_draw_different_variates():
+    seed = 0x1234_5678_9ABC
+    assert oracle.seed_with_stream(seed, 0) == seed
+    masks = {oracle.sign_mask(oracle.seed_with_stream(seed, k)) for k in range(6)}
+    assert masks == {oracle.sign_mask(seed)}                      # the diagonal ignores the stream ...
+    assert oracle.sign_mask(seed + 1) != oracle.sign_mask(seed)   # ... but not the base seed
+    n = 1 << 16
+    u = [oracle.rand32_array(oracle.seed_with_stream(seed, k), 0, n).astype(np.float64) / 2.0**32 for k in range(6)]
+    for a in range(6):
+        for b in range(a + 1, 6):
+            assert (u[a] == u[b]).mean() < 1e-3
+            assert abs(np.corrcoef(u[a], u[b])[0, 1]) < 5 / math.sqrt(n)
+
+
+def torch_bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
+
+
+def _bias_matrix(n):
+    # 4.0 wherever a row or column index is a multiple of 32, else 1.25: every 32-block along either axis has
+    # maximum 4 (scale 1), 4.0 is on the FP4 grid and 1.25 lies exactly between 1 and 1.5
+    p = np.full((n, n), 1.25, dtype=np.float32)
+    p[::32, :] = 4.0
+    p[:, ::32] = 4.0
+    return p
+
+
+def test_stochastic_rounding_of_a_gemm_is_unbiased_where_the_operand_rows_coincide():
+    # Sec. 3.1 tries stochastic rounding because it is unbiased.  For out[i][j] = sum_c A[i][c] B[j][c] the
+    # counter of A[i][c] is i*C + c and that of B[j][c] is j*C + c: at i == j both operands would draw the same
+    # variate if they shared one stream, round the same way, and E[Q(a)Q(b)] = E[Q(a)^2] > a^2.  Each operand
+    # of the three stages therefore rounds under its own stream.  X = W = dY = P (128 x 128) makes every
+    # diagonal entry of Y, dX and dW such a case.
+    n = 128
+    p = _bias_matrix(n)
+    pb = synth.as_u16(torch_bf16(p))
+    exact = p.astype(np.float64) @ p.astype(np.float64).T          # P is symmetric: the same for all three stages
+    d = {"Y": [], "dX": [], "dW": [], "planted": []}
+    for seed in range(24):
+        y, _ = oracle.linear_fwd(pb, pb, oracle.HAD_NONE, oracle.SR, seed)
+        (dx, _), (dw, _) = oracle.linear_bwd(pb, pb, pb, oracle.HAD_NONE, oracle.SR, seed)
+        d["Y"].append(np.diag(y - exact))
+        d["dX"].append(np.diag(dx - exact))
+        d["dW"].append(np.diag(dw - exact))
+        # the mistake this test is there to catch, planted here: both operands under one stream
+        q, s = oracle.quantize(pb, oracle.AXIS_LAST, oracle.HAD_NONE, oracle.SR, seed)
+        d["planted"].append(np.diag(oracle.gemm(q, s, q, s)[0] - exact))
+    for name in ("Y", "dX", "dW"):
+        e = np.concatenate(d[name])
+        assert abs(e.mean()) < 5 * e.std() / math.sqrt(e.size), (name, e.mean(), e.std())
+    e = np.concatenate(d["planted"])
+    assert e.mean() > 20 * e.std() / math.sqrt(e.size)             # 0.0625 per element, 120 elements per sum
+
+
+# ------------------------------------------------------------ the rotation's rounding order (App. A.2)
+def _rotate_stage_by_stage(x32, variant):
+    """One 32-point rotation in numpy float32, every operation written out and rounded on its own.
+    variant 'ref': butterflies h = 1, 2, 4, 8, 16, then ONE multiply by fl32(2^-2.5) = 0x3E3504F3;
+    'scale_first': the multiply before the butterflies; 'ulp_down' / 'ulp_up': the constant one ulp off;
+    'stages_reversed': butterflies h = 16 .. 1."""
+    c_bits = {"ulp_down": 0x3E3504F2, "ulp_up": 0x3E3504F4}.get(variant, 0x3E3504F3)
+    c = np.array([c_bits], dtype=np.uint32).view(np.float32)[0]
+    v = [np.float32(t) for t in x32]
+    if variant == "scale_first":
+        v = [np.float32(t * c) for t in v]
+    hs = (16, 8, 4, 2, 1) if variant == "stages_reversed" else (1, 2, 4, 8, 16)
+    for h in hs:
+        for i in range(32):
+            if (i & h) == 0:
+                a, b = v[i], v[i + h]
+                v[i] = np.float32(a + b)
+                v[i + h] = np.float32(a - b)
+    if variant != "scale_first":
+        v = [np.float32(t * c) for t in v]
+    return np.array(v, dtype=np.float32)
+
+
+def _codes_of_rotated(v):
+    amax_bits = int(np.abs(v).max().view(np.uint32))
+    sb = oracle.e8m0_from_amax_bits(amax_bits)
+    codes = [oracle.e2m1_encode_rne(math.ldexp(float(t), 127 - sb)) for t in v]
+    return sb, np.array(codes, dtype=np.uint8)
+
+
+def test_rotation_rounds_after_every_butterfly_and_multiplies_once_at_the_end(golden_dir):
+    # tests/golden/rotation_sensitive_blocks.txt holds input blocks found (by a seeded numpy search, see
+    # tests/golden/make_rotation_blocks.py) to sit next to a rounding threshold: moving the multiply in front of
+    # the butterflies, a constant one ulp off, or another stage order changes at least one of their FP4 codes.
+    # Every variant is recomputed here stage by stage; on every block the oracle must produce the codes of the
+    # reference order (each fp32 add/sub rounded, stages h = 1..16, one multiply by 0x3E3504F3 last), and every
+    # planted variant must be told apart from it on the blocks listed for it.
+    told_apart = {"scale_first": 0, "ulp_down": 0, "ulp_up": 0, "stages_reversed": 0}
+    for line in open(os.path.join(golden_dir, "rotation_sensitive_blocks.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        variant, *hexes = line.split()
+        x = np.array([int(h, 16) for h in hexes], dtype=np.uint16)
+        assert x.size == 32
+        x32 = bits_to_f64(x).astype(np.float32)
+        sb_ref, codes_ref = _codes_of_rotated(_rotate_stage_by_stage(x32, "ref"))
+        sb_v, codes_v = _codes_of_rotated(_rotate_stage_by_stage(x32, variant))
+        if sb_v != sb_ref or not np.array_equal(codes_v, codes_ref):
+            told_apart[variant] += 1
+        q, s = oracle.quantize(x.reshape(1, 32), had=oracle.HAD_DET)
+        assert int(s[0, 0]) == sb_ref, variant
+        assert np.array_equal(unpack(q)[0], codes_ref), variant
+    assert all(n >= 3 for n in told_apart.values()), told_apart

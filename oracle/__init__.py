@@ -26,11 +26,23 @@ RNE, SR = 0, 1
 FMT_E2M1, FMT_E4M3 = 0, 1
 
 
+# MXFP4_ORACLE_SANITIZE=1 builds and loads an AddressSanitizer + UndefinedBehaviorSanitizer build of the oracle
+# instead (the interpreter must then be started with the ASan runtime preloaded):
+#   MXFP4_ORACLE_SANITIZE=1 LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+#       python -m pytest tests -q -m "not gpu"
+_SANITIZE = os.environ.get("MXFP4_ORACLE_SANITIZE", "") not in ("", "0")
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libmxfp4_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (no fast-math, no FMA contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
                "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        if _SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                        "-fno-omit-frame-pointer"]
         subprocess.run(cmd, check=True)
     return _LIB
 

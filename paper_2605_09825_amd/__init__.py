@@ -13,6 +13,8 @@ from typing import Optional, Tuple
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmxfp4.so")
+if os.environ.get("MXFP4_SANITIZE_HOST", "") not in ("", "0"):  # host-sanitizer build (see build.py)
+    LIB_PATH = os.path.join(HERE, "libmxfp4_san.so")
 
 # enums of include/mxfp4.h
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EDEVICE, ENOTIMPL = range(7)

@@ -25,6 +25,18 @@ def hipcc() -> str:
     return exe
 
 
+# MXFP4_SANITIZE_HOST=1: an AddressSanitizer + UndefinedBehaviorSanitizer build of the HOST side of the library
+# (argument checks, layouts, launch logic; device code is not instrumented) as libmxfp4_san.so, which the
+# binding then loads instead.  Run the CPU-only tests against it with the clang ASan runtime preloaded:
+#   MXFP4_SANITIZE_HOST=1 LD_PRELOAD=$(ls /opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so) \
+#       ASAN_OPTIONS=detect_leaks=0 python -m pytest tests/test_abi.py -q
+SANITIZE_HOST = os.environ.get("MXFP4_SANITIZE_HOST", "") not in ("", "0")
+if SANITIZE_HOST:
+    LIB = os.path.join(HERE, "libmxfp4_san.so")
+    FLAGS = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host",
+                                                "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
 def build(verbose: bool = False) -> str:
     """Compile every HIP source into paper_2605_09825_amd/libmxfp4.so (always recompiles)."""
     cmd = [hipcc()] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]

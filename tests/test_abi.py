@@ -200,3 +200,15 @@ def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
     monkeypatch.setattr(mx, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         mx.lib()
+
+
+def test_static_scratch_forward_argument_errors(L):
+    # the call that allocates nothing: sizes beyond its 32 MiB array and bad arguments are refused on the host
+    cfg = mx.make_cfg(mx.HAD_DET, mx.RNE, 0)
+    f = L.mxfp4_linear_fwd_static
+    assert L.mxfp4_linear_workspace_bytes(8192, 6144, 4096, ctypes.byref(cfg), 0) <= mx.STATIC_SCRATCH_BYTES
+    assert f(P, P, P, 16384, 6144, 4096, ctypes.byref(cfg), None) == mx.EWORKSPACE
+    assert f(P, P, P, 1 << 40, 1 << 40, 1 << 40, ctypes.byref(cfg), None) == mx.EWORKSPACE
+    assert f(P, P, P, 64, 64, 48, ctypes.byref(cfg), None) == mx.ESHAPE
+    assert f(None, P, P, 64, 64, 64, ctypes.byref(cfg), None) == mx.EINVAL
+    assert f(P, P, P, 64, 64, 64, None, None) == mx.EINVAL

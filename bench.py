@@ -11,9 +11,13 @@ mxfp4_linear_fwd + mxfp4_linear_bwd (5 quantiser launches) is timed as well and 
 `separate_calls_ms_per_step`.  Inputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` = 3 * 2*M*N*K flop / step time, i.e. GEMM TFLOP/s including the
-rotation and quantisation time.  `roofline` describes the dominant kernel (the FP4 GEMM)
-against the dense MXFP4 MFMA peak; `quantizer` the fused rotate+quantise kernels against peak
-HBM bandwidth (measured on a rotation of buffers larger than the 256 MB last-level cache);
+rotation and quantisation time; the timed region of `--steps` steps is repeated 7 times after the warm-up
+and the median repetition is reported (minimum and maximum beside it), after the per-kernel legs have
+already run, so that clocks still ramping at the start of the process cannot move it.  `roofline` describes
+the dominant kernel (the FP4 GEMM) against the dense MXFP4 MFMA peak, with the shader clock sampled
+during a sustained run of that kernel; `quantizer` the fused rotate+quantise kernels against peak
+HBM bandwidth (measured on a rotation of buffers larger than the 256 MB last-level cache), for no
+rotation, H16 and H32; `configs` the totals of the other four benchmark configurations;
 `cpu_baseline` the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -33,10 +37,15 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 BYTES_PER_ELEM = 2.0 + 0.5 + 1.0 / 32.0  # bf16 read + packed codes + scale byte per element
 BYTES_PER_ELEM_DUAL = 2.0 + 2 * (0.5 + 1.0 / 32.0)  # one read, both quantisations written
 
-# Bytes crossing the L2's outward port per GEMM (mean of the three GEMMs of a step), from the FETCH_SIZE and
-# WRITE_SIZE runs summarised in profiles/qkv_traffic_counters.md (FETCH_SIZE x 2.0 after calibration
-# against a 256 MiB copy)
+# Bytes crossing the L2's outward port per GEMM launch (mean of the three GEMMs of a step): not measured in this
+# run but taken from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in the file named below (FETCH_SIZE
+# x 2.0 after calibration against a 256 MiB copy).  They include what the 256 MB Infinity Cache serves.
 GEMM_TRAFFIC_BYTES = 290.8e6
+GEMM_TRAFFIC_SOURCE = "profiles/qkv_traffic_counters.md"
+# operands once + output once, mean of Fprop (bf16 out), Dgrad (bf16 out), Wgrad (fp32 out)
+GEMM_ALGORITHMIC_BYTES = ((M * K + N * K) * 0.53125 + M * N * 2 + (M * N + K * N) * 0.53125 + M * K * 2 +
+                          (N * M + K * M) * 0.53125 + N * K * 4) / 3.0
+REPEATS = 7  # repetitions of the timed region; the median is reported
 
 
 def event_time_ms(fn, iters, torch):
@@ -51,7 +60,60 @@ def event_time_ms(fn, iters, torch):
     return start.elapsed_time(stop) / iters
 
 
-def other_config(args, torch, mx, synth) -> int:
+class ClockSampler:
+    """Samples the shader clock (MHz) and the socket power (W) from sysfs a few times a second in a thread while
+    a leg runs (the boxes do not let an ordinary user pin clocks, so the clock the kernel actually ran at is
+    reported beside the spec-peak fraction)."""
+
+    def __init__(self, period_s=0.05):
+        import glob
+        self.period = period_s
+        self.sclk_files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.power_files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average") +
+                                  glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.sclk, self.power = [], []
+        self._stop = False
+        self._th = None
+
+    def _read(self):
+        try:
+            for line in open(self.sclk_files[0]):
+                if line.rstrip().endswith("*"):
+                    self.sclk.append(float(line.split(":")[1].strip().rstrip("*").strip().lower().replace("mhz", "")))
+        except Exception:
+            pass
+        try:
+            self.power.append(float(open(self.power_files[0]).read()) * 1e-6)
+        except Exception:
+            pass
+
+    def __enter__(self):
+        import threading
+
+        def loop():
+            while not self._stop:
+                self._read()
+                time.sleep(self.period)
+        self._th = threading.Thread(target=loop, daemon=True)
+        self._th.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        self._th.join()
+
+    @staticmethod
+    def _median(v):
+        v = sorted(v)
+        return v[len(v) // 2] if v else None
+
+    def summary(self):
+        return {"sclk_mhz_median": self._median(self.sclk), "sclk_mhz_min": min(self.sclk) if self.sclk else None,
+                "sclk_mhz_max": max(self.sclk) if self.sclk else None, "samples": len(self.sclk),
+                "power_w_median": self._median(self.power)}
+
+
+def other_config(args, torch, mx, synth, emit=True):
     """Timing of the benchmark configurations other than the headline one (1, 3, 4, 5): one JSON line each,
     same conventions (inputs resident, rotation and quantisation inside the timed region)."""
     dev = torch.device("cuda:0")
@@ -61,11 +123,14 @@ def other_config(args, torch, mx, synth) -> int:
             fn()
         torch.cuda.synchronize()
         n = max(args.steps // 10, 5)
-        t0 = time.perf_counter()
-        for _ in range(n):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / n
+        reps = []
+        for _ in range(3):  # median of three repetitions of the timed region
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            reps.append((time.perf_counter() - t0) * 1e3 / n)
+        return sorted(reps)[1]
 
     def layer(Ml, Kl, Nl, had, rnd, x, w, dy, stages="fdw"):
         cfg = mx.make_cfg(had, rnd, 2024, y_dtype=mx.OUT_BF16, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32)
@@ -133,6 +198,8 @@ def other_config(args, torch, mx, synth) -> int:
         "parts": [{"what": n, "ms": round(ms, 4), "tflops_incl_quant": round(f / (ms * 1e-3) / 1e12, 1)}
                   for n, ms, f in rows],
     }
+    if not emit:
+        return out
     print(json.dumps(out))
     return 0
 
@@ -192,6 +259,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the totals of configurations 1, 3, 4 and 5 (the `configs` array)")
     ap.add_argument("--counter-run", action="store_true",
                     help="for rocprofv3 --pmc: one 256 MiB device copy (known traffic) followed by one "
                          "step through the training pair and one through the separate calls, no timing, "
@@ -251,25 +320,7 @@ def main() -> int:
         print("counter run done: reference copy 268435456 bytes each way, then 2 steps")
         return 0
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    for _ in range(2):
-        step_separate()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step_separate()
-    torch.cuda.synchronize()
-    ms_separate = (time.perf_counter() - t0) * 1e3 / args.steps
     flop_step = 3 * 2.0 * M * N * K
-    tflops_incl = flop_step / (ms_per_step * 1e-3) / 1e12
 
     # ---- per-kernel durations, live, with events on the launch stream -------------------------
     # (torch's current stream is the stream every call above was launched on)
@@ -400,13 +451,88 @@ def main() -> int:
     fp8_rot(mx.AXIS_FIRST)()
     t_fp8_rows = event_time_ms(fp8_rot(mx.AXIS_LAST), n_rot, torch)
     t_fp8_cols = event_time_ms(fp8_rot(mx.AXIS_FIRST), n_rot, torch)
-    del rot
     gbs = lambda n_el, ms, bpe=BYTES_PER_ELEM: n_el * bpe / (ms * 1e-3) / 1e9
+
+    # the same three kernels under each rotation size (Table 1 note: H16 against H32), HBM-resident
+    def rot_call(kind, had):
+        def run():
+            t = rot[state["i"] % len(rot)]
+            state["i"] += 1
+            if kind == "rows":
+                mx.mxfp4_quantize(t, mx.AXIS_LAST, had, mx.RNE, 0, q=xq, s=xs)
+            elif kind == "cols":
+                mx.mxfp4_quantize(t, mx.AXIS_FIRST, had, mx.RNE, 0, q=xtq, s=xts)
+            else:
+                rc = L.mxfp4_quantize_dual(t.data_ptr(), M, K, K, had, mx.RNE, 0, xq.data_ptr(), xs.data_ptr(),
+                                           xtq.data_ptr(), xts.data_ptr(), st)
+                assert rc == mx.OK
+        return run
+
+    by_rotation = {}
+    for kind, bpe in (("rows", BYTES_PER_ELEM), ("cols", BYTES_PER_ELEM), ("dual", BYTES_PER_ELEM_DUAL)):
+        by_rotation[kind] = {}
+        for name, had in (("none", mx.HAD_NONE), ("h16", mx.HAD_DET16), ("h32", mx.HAD_DET)):
+            fn = rot_call(kind, had)
+            fn()
+            ms = event_time_ms(fn, n_rot, torch)
+            by_rotation[kind][name] = {"launch_ms": round(ms, 4), "achieved": round(gbs(M * K, ms, bpe), 1),
+                                       "frac": round(gbs(M * K, ms, bpe) / PEAK_HBM_GBS, 4)}
+        by_rotation[kind]["h16_speedup_over_h32"] = round(by_rotation[kind]["h32"]["launch_ms"] /
+                                                          by_rotation[kind]["h16"]["launch_ms"], 3)
+    del rot
     quant_rows_gbs, quant_cols_gbs = gbs(M * K, t_rows_cold), gbs(M * K, t_cols_cold)
     quant_dual_gbs = gbs(M * K, t_dual_cold, BYTES_PER_ELEM_DUAL)
     quant_2d_gbs = gbs(M * K, t_2d_cold, BYTES_PER_ELEM_DUAL)
     bpe8 = 2.0 + 1.0 + 1.0 / 32.0  # bf16 read + one E4M3 byte + scale byte per element
     fp8_rows_gbs, fp8_cols_gbs = gbs(M * K, t_fp8_rows, bpe8), gbs(M * K, t_fp8_cols, bpe8)
+
+    # ---- shader clock during a sustained run of the dominant kernel ---------------------------------------
+    # (about a second of back-to-back launches of the step's three GEMMs on the step's operands)
+    def gemm_round():
+        launches[2][1]()
+        launches[4][1]()
+        launches[5][1]()
+    for _ in range(20):
+        gemm_round()
+    torch.cuda.synchronize()
+    with ClockSampler() as cs:
+        t0 = time.perf_counter()
+        n_rounds = 0
+        while time.perf_counter() - t0 < 1.0:
+            for _ in range(100):
+                gemm_round()
+            torch.cuda.synchronize()
+            n_rounds += 100
+        t_sustained = (time.perf_counter() - t0) * 1e3 / (3 * n_rounds)
+    clock = cs.summary()
+    sclk = clock["sclk_mhz_median"]
+    gemm_tflops_sustained = 2.0 * M * N * K / (t_sustained * 1e-3) / 1e12
+    peak_at_clock = PEAK_FP4_TFLOPS * sclk / 2400.0 if sclk else None
+
+    # ---- the headline: the whole step, timed last (the legs above have brought the chip to its working state) --
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    reps = []
+    for _ in range(REPEATS):
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        reps.append((time.perf_counter() - t0) * 1e3 / args.steps)
+    ms_per_step = sorted(reps)[REPEATS // 2]
+    for _ in range(5):
+        step_separate()
+    torch.cuda.synchronize()
+    reps_sep = []
+    for _ in range(3):
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_separate()
+        torch.cuda.synchronize()
+        reps_sep.append((time.perf_counter() - t0) * 1e3 / args.steps)
+    ms_separate = sorted(reps_sep)[1]
+    tflops_incl = flop_step / (ms_per_step * 1e-3) / 1e12
 
     out = {
         "metric": "mxfp4_linear_gemm_tflops_incl_hadamard_quantize",
@@ -416,13 +542,18 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "repeats": REPEATS,
+        "ms_per_step_min": round(min(reps), 4),
+        "ms_per_step_max": round(max(reps), 4),
+        "timing": f"median of {REPEATS} repetitions of the timed region of `steps` steps, after `warmup` steps; "
+                  "the per-kernel legs run before it",
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "fp4",
         "data": "synthetic",
         "config": {
-            "workload": "Llama-3.1-8B fused QKV linear, Fprop+Dgrad+Wgrad, M=8192 K=4096 N=6144, "
+            "workload": "config 2: Llama-3.1-8B fused QKV linear, Fprop+Dgrad+Wgrad, M=8192 K=4096 N=6144, "
                         "deterministic H32 + MXFP4 RNE on both operands of each GEMM; y,dx bf16, dw fp32",
             "M": M, "K": K, "N": N, "launches_per_step": 5,
             "calls": "mxfp4_linear_fwd_save + mxfp4_linear_bwd_saved",
@@ -437,6 +568,15 @@ def main() -> int:
             "unit": "TFLOP/s",
             "frac": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
             "traffic": GEMM_TRAFFIC_BYTES,
+            "traffic_source": GEMM_TRAFFIC_SOURCE + " (rocprofv3 FETCH_SIZE + WRITE_SIZE at the L2's outward port, "
+                              "Infinity Cache hits included; not measured in this run)",
+            "algorithmic_bytes": round(GEMM_ALGORITHMIC_BYTES),
+            "traffic_over_algorithmic": round(GEMM_TRAFFIC_BYTES / GEMM_ALGORITHMIC_BYTES, 2),
+            "sclk_mhz": sclk,
+            "clock_samples": clock,
+            "sustained_tflops": round(gemm_tflops_sustained, 2),
+            "peak_at_measured_clock": round(peak_at_clock, 1) if peak_at_clock else None,
+            "frac_at_measured_clock": round(gemm_tflops_sustained / peak_at_clock, 4) if peak_at_clock else None,
             "launch_ms": {"fprop": round(t_fprop, 4), "dgrad": round(t_dgrad, 4), "wgrad": round(t_wgrad, 4)},
             "in_step_bracket_ms": {k: round(t_k[k], 4) for k in ("fprop", "dgrad", "wgrad")},
         },
@@ -457,6 +597,7 @@ def main() -> int:
                                         "launch_ms": round(t_fp8_rows, 4), "bytes_per_element": bpe8},
             "mxfp8_cols_hbm_resident": {"achieved": round(fp8_cols_gbs, 1), "frac": round(fp8_cols_gbs / PEAK_HBM_GBS, 4),
                                         "launch_ms": round(t_fp8_cols, 4), "bytes_per_element": bpe8},
+            "by_rotation_hbm_resident": by_rotation,
             "in_step_ms": {k: round(v, 4) for k, v in t_q.items()},
             "in_step_gbs_cache_warm": {k: round(gbs(elems[k], t_q[k]), 1) for k in elems},
         },
@@ -464,6 +605,21 @@ def main() -> int:
                          "quantize_total": round(t_quant_total, 4),
                          "note": "event brackets inside a second timed region; each includes the dispatch gap"},
     }
+
+    if not args.no_other_configs:
+        # totals of the other benchmark configurations, same conventions (free the headline's buffers first)
+        del x, w, dy, y, dx, dw, ws_f, ws_b, saved, xq, xs, wq, wsc, gq, gs, wtq, wts, gtq, gts, xtq, xts
+        del sv_wtq, sv_wts, sv_xtq, sv_xts, launches
+        torch.cuda.empty_cache()
+        out["configs"] = []
+        for c in (1, 3, 4, 5):
+            args.config = c
+            r = other_config(args, torch, mx, synth, emit=False)
+            out["configs"].append({"config": c, "workload": r["config"]["workload"], "ms": r["ms_per_step"],
+                                   "tflops_incl_quant": r["value"],
+                                   "pct_of_fp4_peak_incl_quant": r["pct_of_fp4_peak_incl_quant"], "parts": r["parts"]})
+            torch.cuda.empty_cache()
+        args.config = 2
 
     if not args.no_cpu_baseline:
         import oracle

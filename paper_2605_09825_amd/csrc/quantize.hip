@@ -113,21 +113,17 @@ __device__ __forceinline__ void rotate_block(float (&v)[32], uint32_t sign_mask)
     }
 }
 
-// Block maximum on the bit patterns (NaN and infinity compare above every finite value), without
-// clearing 32 sign bits: the unsigned maximum is the largest-magnitude negative value if there is
-// one, the signed maximum (from 0) the largest positive one.
+// Bit pattern of the block's largest magnitude.  V_MAXIMUM3_F32 (two new values per instruction, |.| as source
+// modifiers) returns NaN if any input is NaN, so a NaN or an infinity anywhere in the block shows as an exponent
+// field of 255, as in a comparison of the bit patterns.
 __device__ __forceinline__ uint32_t amax_bits(const float (&v)[32])
 {
-    uint32_t mu = 0;
-    int32_t mi = 0;
+    float m = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-        const uint32_t b = __float_as_uint(v[i]);
-        mu = b > mu ? b : mu;
-        mi = (int32_t)b > mi ? (int32_t)b : mi;
-    }
-    mu &= 0x7FFFFFFFu;
-    return (uint32_t)mi > mu ? (uint32_t)mi : mu;
+    for (int i = 0; i < 32; i += 2)
+        m = __builtin_elementwise_maximum(
+            __builtin_elementwise_maximum(__builtin_fabsf(v[i]), __builtin_fabsf(v[i + 1])), m);
+    return __float_as_uint(m) & 0x7FFFFFFFu;
 }
 
 // FP4 codes of one rotated block under the scale that follows from the shared maximum `amax` (bit
@@ -459,7 +455,9 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
         reinterpret_cast<uint4 *>(lds + w * (SLICE + SKEW))[2 * lane + j] = codes;
         lds_s[2 * lane + j][w] = (uint8_t)sb;
     }
-    __syncthreads();
+    // workgroup barrier for the LDS traffic only: unlike __syncthreads() it does not make the wave wait for its
+    // outstanding global stores (the row-wise output, which nobody in the workgroup reads back)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     // each output row (input column) receives its 8 x 16 bytes from 8 consecutive lanes
     const int ch = tid & 7;

@@ -166,7 +166,11 @@ def test_blocks_that_expose_the_rotation_rounding_order(golden_dir):
     for had in (mx.HAD_DET, mx.HAD_RANDSIGN):
         check(blocks, mx.AXIS_LAST, had, mx.RNE, seed=0 if had == mx.HAD_DET else 99)
     check(blocks.t().contiguous(), mx.AXIS_FIRST, mx.HAD_DET, mx.RNE)
-    ql, sl, qf, sf = mx.mxfp4_quantize_dual(blocks.t().contiguous().to("cuda:0"), mx.HAD_DET)   # [32][16]: both ways
+    # both ways at once: the blocks as the 32 columns of a 32 x 32 tensor (the 16 of them twice)
+    sq = torch.cat([blocks, blocks], dim=0).t().contiguous()
+    ql, sl, qf, sf = mx.mxfp4_quantize_dual(sq.to("cuda:0"), mx.HAD_DET)
     torch.cuda.synchronize()
-    qo, so = oracle.quantize(synth.as_u16(blocks), oracle.AXIS_LAST, oracle.HAD_DET)
+    qo, so = oracle.quantize(synth.as_u16(sq), oracle.AXIS_FIRST, oracle.HAD_DET)
     assert np.array_equal(qf.cpu().numpy(), qo) and np.array_equal(sf.cpu().numpy(), so)
+    qo, so = oracle.quantize(synth.as_u16(sq), oracle.AXIS_LAST, oracle.HAD_DET)
+    assert np.array_equal(ql.cpu().numpy(), qo) and np.array_equal(sl.cpu().numpy(), so)

@@ -113,6 +113,67 @@ class ClockSampler:
                 "power_w_median": self._median(self.power)}
 
 
+def power_probe(args, torch, mx) -> int:
+    """Shader clock and socket power while the tiled GEMM runs back to back on the headline shape, for operand
+    codes that are (a) all zero, (b) uniformly random bytes, (c) the quantised N(0,1) / N(0,0.02) tensors of the
+    benchmark: plain text, one block per case (the evidence behind `frac_at_measured_clock`)."""
+    from paper_2605_09825_amd import synth
+    dev = torch.device("cuda:0")
+    Ra, Rb, C = M, N, K
+    out = torch.empty((Ra, Rb), dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+
+    def operands(kind):
+        if kind == "zero codes":
+            aq = torch.zeros((Ra, C // 2), dtype=torch.uint8, device=dev)
+            bq = torch.zeros((Rb, C // 2), dtype=torch.uint8, device=dev)
+        elif kind == "random codes":
+            aq = torch.randint(0, 256, (Ra, C // 2), dtype=torch.uint8, device=dev, generator=gen)
+            bq = torch.randint(0, 256, (Rb, C // 2), dtype=torch.uint8, device=dev, generator=gen)
+        else:
+            x = synth.normal(Ra, C, 1.0, 0, synth.STREAM_X).to(dev)
+            w = synth.normal(Rb, C, 0.02, 0, synth.STREAM_W).to(dev)
+            aq, as_ = mx.mxfp4_quantize(x, mx.AXIS_LAST, mx.HAD_DET)
+            bq, bs = mx.mxfp4_quantize(w, mx.AXIS_LAST, mx.HAD_DET)
+            return aq, as_, bq, bs
+        as_ = torch.full((Ra, C // 32), 127, dtype=torch.uint8, device=dev)
+        bs = torch.full((Rb, C // 32), 127, dtype=torch.uint8, device=dev)
+        return aq, as_, bq, bs
+
+    print(f"# tiled MXFP4 GEMM {Ra} x {Rb} x {C}, bf16 out, back-to-back launches for {args.probe_seconds} s per case;")
+    print("# shader clock from pp_dpm_sclk, socket power from hwmon, one sample every 50 ms")
+    for kind in ("zero codes", "random codes", "quantised benchmark tensors (H32, RNE)"):
+        aq, as_, bq, bs = operands(kind)
+        for _ in range(50):
+            mx.mxfp4_gemm(aq, as_, bq, bs, out=out, out_dtype=mx.OUT_BF16)
+        torch.cuda.synchronize()
+        n = 0
+        with ClockSampler() as cs:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            t0 = time.perf_counter()
+            while time.perf_counter() - t0 < args.probe_seconds:
+                for _ in range(200):
+                    mx.mxfp4_gemm(aq, as_, bq, bs, out=out, out_dtype=mx.OUT_BF16)
+                torch.cuda.synchronize()
+                n += 200
+            e1.record()
+            e1.synchronize()
+        us = e0.elapsed_time(e1) / n * 1e3
+        tf = 2.0 * Ra * Rb * C / us / 1e6
+        c = cs.summary()
+        sclk = c["sclk_mhz_median"]
+        at_clock = tf / (PEAK_FP4_TFLOPS * sclk / 2400.0) if sclk else float("nan")
+        print(f"{kind}: {us:.1f} us per GEMM = {tf:.0f} TFLOP/s = {tf / PEAK_FP4_TFLOPS:.3f} of the 10.1 PFLOP/s peak; "
+              f"sclk median {sclk} MHz (min {c['sclk_mhz_min']}, max {c['sclk_mhz_max']}, {c['samples']} samples), "
+              f"power median {c['power_w_median']} W; fraction of the peak at that clock {at_clock:.3f}")
+        k = max(1, len(cs.sclk) // 12)
+        print("    sclk MHz:", " ".join(f"{v:.0f}" for v in cs.sclk[::k]))
+        print("    power W: ", " ".join(f"{v:.0f}" for v in cs.power[::k]))
+    return 0
+
+
 def other_config(args, torch, mx, synth, emit=True):
     """Timing of the benchmark configurations other than the headline one (1, 3, 4, 5): one JSON line each,
     same conventions (inputs resident, rotation and quantisation inside the timed region)."""
@@ -261,6 +322,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the totals of configurations 1, 3, 4 and 5 (the `configs` array)")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="print shader clock and socket power sampled while the GEMM runs on zero, random and "
+                         "benchmark operands (text, no JSON)")
+    ap.add_argument("--probe-seconds", type=float, default=3.0)
     ap.add_argument("--counter-run", action="store_true",
                     help="for rocprofv3 --pmc: one 256 MiB device copy (known traffic) followed by one "
                          "step through the training pair and one through the separate calls, no timing, "
@@ -281,6 +346,8 @@ def main() -> int:
     mx.lib()  # fail loudly now if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.power_probe:
+        return power_probe(args, torch, mx)
     if args.ladder:
         return ladder(args, torch, mx, synth)
     if args.config != 2:

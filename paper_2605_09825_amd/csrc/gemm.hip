@@ -213,7 +213,11 @@ struct TileSrc {
 // and 32 + 16h .. +15 of its 64 (probed), which are exactly the two 16-byte fragments the E2M1 path fetches
 // for its K-steps 2j and 2j+1: so data movement, LDS layout and fragment reads are the same for both formats,
 // and only the matrix instructions differ (16 per two phases instead of 16 per phase, taking two fragments).
-template <bool OUT_FP32, bool ACC, int FMT>
+// NJ: 32-column groups of a wave's sub-tile.  4: the 256 x 256 tile (wave sub-tile 128 x 128, 16 matrix
+// instructions per K-step).  2 (E2M1 only): a 256 x 128 tile (sub-tile 128 x 64, 8 instructions per K-step) for
+// outputs that have too few 256 x 256 tiles to fill the chip, and for the part-filled last round of others;
+// it moves 1.5 times the operand bytes per flop, so it is only used where compute units would idle otherwise.
+template <bool OUT_FP32, bool ACC, int FMT, int NJ>
 __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, const uint8_t *__restrict__ as,
                                                const uint8_t *__restrict__ bq, const uint8_t *__restrict__ bs,
                                                int64_t C, void *__restrict__ out, int64_t ld, int tiles_m,
@@ -221,6 +225,11 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
                                                uint8_t *const smem, const uint32_t lds0)
 {
 
+    static_assert(NJ == 4 || (NJ == 2 && FMT == 0), "the narrow tile is built for E2M1 operands only");
+    constexpr int TILE_N = 64 * NJ;          // B rows (output columns) per tile
+    constexpr int BROWS = TILE_N / 4;        // B rows one wave loads per stage: 64 or 32
+    constexpr int NLOADS = 8 + BROWS / 8;    // direct-to-LDS loads per wave and stage: 16 or 12
+    constexpr int NSLOT = 4 * NJ;            // matrix instructions per K-step
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
@@ -248,11 +257,11 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         const int in = L - grp * span;
         TileSrc t;
         t.m0 = (int64_t)(first + in % gm) * TILE;
-        t.n0 = (int64_t)(in / gm) * TILE;
+        t.n0 = (int64_t)(in / gm) * TILE_N;
         t.a = aq + (t.m0 + wave * 64) * rowbytes;
-        t.b = bq + (t.n0 + wave * 64) * rowbytes;
+        t.b = bq + (t.n0 + wave * BROWS) * rowbytes;
         t.as = as + (t.m0 + wave * 64) * nkb;
-        t.bs = bs + (t.n0 + wave * 64) * nkb;
+        t.bs = bs + (t.n0 + wave * BROWS) * nkb;
         return t;
     };
     if (lw >= count_x) return;  // (whole workgroup: nothing to do)
@@ -265,18 +274,22 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #pragma unroll
     for (int g = 0; g < 8; ++g)  // (less the immediate offset (g - 4) KiB the load instruction adds back)
         dvo[g] = (uint32_t)((8 * g + drr) * rowbytes) + (uint32_t)((dcc ^ drr ^ (g & 1)) << 4) - (uint32_t)((g - 4) * 1024);
-    const uint32_t lds_wave = lds0 + (uint32_t)wave * 8192u;  // the wave's 8 x 1 KiB of each operand's stage slice
+    // the wave's 8 x 1 KiB of A's stage slice and 8 (narrow tile: 4) x 1 KiB of B's
+    const uint32_t lds_wave_a = lds0 + OFF_A + (uint32_t)wave * 8192u;
+    const uint32_t lds_wave_b = lds0 + OFF_B + (uint32_t)wave * (uint32_t)(BROWS * 128);
     const uint32_t svoff = (uint32_t)((lane >> 1) * nkb) + (uint32_t)((lane & 1) << 4);
 
     // load n (0..15) of stage s of tile t for this wave, in issue order: n = 0..3 A's 8-row groups 0..3,
-    // 4..7 B's groups 0..3, 8..11 A's groups 4..7, 12..15 B's groups 4..7.  The four loads of a run share one M0
+    // 4..7 B's groups 0..3, 8..11 A's groups 4..7, 12..15 B's groups 4..7 (the narrow tile has no 12..15: a
+    // wave loads only 32 rows of B).  The four loads of a run share one M0
     // (the LDS address of the operand's group 4; the groups sit at immediate offsets (g - 4) KiB from it);
     // `force` makes a load set M0 itself (where scale loads, which set their own, are issued in between).
     auto issue_load = [&](const TileSrc &t, int s, int buf, auto nc, auto force) {
         constexpr int n = decltype(nc)::value, op = (n >> 2) & 1, g = (n >> 3) * 4 + (n & 3);
+        static_assert(n < NLOADS, "no such load for this tile shape");
         constexpr bool setm0 = decltype(force)::value || (n & 3) == 0;
         const int64_t koff = (int64_t)s * (STAGE_K / 2);
-        dma16_run<(g - 4) * 1024, setm0>(lds_wave + buf * STAGE_BYTES + (op ? OFF_B : OFF_A) + 4096, dvo[g],
+        dma16_run<(g - 4) * 1024, setm0>((op ? lds_wave_b : lds_wave_a) + buf * STAGE_BYTES + 4096, dvo[g],
                                          (op ? t.b : t.a) + koff);
     };
     using no_force = std::false_type;
@@ -288,10 +301,15 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // instruction j (0..3) of batch b for this wave: j>>1 = operand, j&1 = which 32 of its 64 rows
     // Batch b of a tile lives in scale buffer (b ^ par) & 1; par alternates between tiles so that
     // a tile's first batch never lands in the buffer its predecessor's last batch is still read from.
+    // (narrow tile: a wave has only 32 rows of B, so instruction 3 repeats instruction 2: the same bytes to the
+    // same place, which keeps the stage bodies free of branches)
     auto scales_dst = [&](int b, int j, int par) {
-        return lds0 + OFF_SC + ((b ^ par) & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES + (wave * 64 + (j & 1) * 32) * 32;
+        if (NJ == 2 && j == 3) j = 2;
+        const int rows0 = (j >> 1) ? wave * BROWS : wave * 64;
+        return lds0 + OFF_SC + ((b ^ par) & 1) * SC_BUF_BYTES + (j >> 1) * SC_OP_BYTES + (rows0 + (j & 1) * 32) * 32;
     };
     auto scales_src = [&](const TileSrc &t, int b, int j) {
+        if (NJ == 2 && j == 3) j = 2;
         return ((j >> 1) ? t.bs : t.as) + (int64_t)(j & 1) * 32 * nkb + batch_first(b) * SC_STAGE;
     };
     auto issue_scales = [&](const TileSrc &t, int b, int j, int par) {
@@ -305,8 +323,9 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     uint32_t foff[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) foff[kk] = fl0 + (uint32_t)((((kk << 1) | fh) ^ fm) << 4);
-    const uint32_t a_frag0 = OFF_A + wm * 16 * 1024, b_frag0 = OFF_B + wn * 16 * 1024;
-    const uint32_t sa_frag0 = OFF_SC + (wm * 128 + fr) * 32, sb_frag0 = OFF_SC + SC_OP_BYTES + (wn * 128 + fr) * 32;
+    const uint32_t a_frag0 = OFF_A + wm * 16 * 1024, b_frag0 = OFF_B + wn * (NJ * 4) * 1024;
+    const uint32_t sa_frag0 = OFF_SC + (wm * 128 + fr) * 32;
+    const uint32_t sb_frag0 = OFF_SC + SC_OP_BYTES + (wn * (32 * NJ) + fr) * 32;
     // scale bytes of one stage -> one register whose byte k is the lane's block in instruction K-step k
     const uint32_t perm_sel = FMT ? (fh ? 0x03010301u : 0x02000200u) : (fh ? 0x07050301u : 0x06040200u);
 
@@ -335,7 +354,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             sa_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i].y, sraw[2 * i].x, perm_sel);
-            sb_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i + 1].y, sraw[2 * i + 1].x, perm_sel);
+            if (i < NJ) sb_cur[i] = (int)__builtin_amdgcn_perm(sraw[2 * i + 1].y, sraw[2 * i + 1].x, perm_sel);
         }
     };
 
@@ -350,7 +369,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // K-step KK selects the scale byte.
 #define MXFP4_MMA(SET, KK, N, FRESH)                                                                            \
     {                                                                                                           \
-        constexpr int i_ = (N) >> 2, j_ = (N) & 3;                                                              \
+        constexpr int i_ = (N) / NJ, j_ = (N) % NJ;                                                             \
         v8i fb8 = {fb[SET][j_].x, fb[SET][j_].y, fb[SET][j_].z, fb[SET][j_].w, 0, 0, 0, 0};                     \
         v8i fa8 = {fa[SET][i_].x, fa[SET][i_].y, fa[SET][i_].z, fa[SET][i_].w, 0, 0, 0, 0};                     \
         acc[i_][j_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb8, fa8, (FRESH) ? zero16 : acc[i_][j_], \
@@ -370,17 +389,29 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // phase P (0..3) of a stage, slot N (0..15): E2M1 issues instruction N of K-step P; E4M3 issues, in even
     // slots, instruction N/2 (+8 in odd phases) of K-step P/2
 #define MXFP4_SLOT_MMA(P, N, FRESH)                                                                             \
-    if (FMT == 0) {                                                                                             \
-        MXFP4_MMA((P) & 1, P, N, FRESH)                                                                         \
-    } else if (((N) & 1) == 0) {                                                                                \
+    if constexpr (FMT == 0) {                                                                                   \
+        if constexpr ((N) < NSLOT) {                                                                            \
+            MXFP4_MMA((P) & 1, P, N, FRESH)                                                                     \
+        }                                                                                                       \
+    } else if constexpr (((N) & 1) == 0) {                                                                      \
         MXFP8_MMA((P) >> 1, ((N) >> 1) + 8 * ((P) & 1), FRESH)                                                  \
     }
 #define MXFP4_PIN() __builtin_amdgcn_sched_barrier(0);
     // E2M1: the 8 fragment reads of a K-step go into the even slots, B0..B3 then A0..A3 (instruction n of the
     // next K-step needs A[n/4] and B[n%4]: every fragment is at least 8 slots old when first used), so that LDS
     // reads alternate with the direct-to-LDS loads of the odd slots instead of arriving in bursts.
-#define MXFP4_FRAG_SLOT(N) (!FMT && ((N) & 1) == 0)
-#define MXFP4_FRAG_OF(N) (((N) >> 1) < 4 ? 2 * ((N) >> 1) + 1 : 2 * (((N) >> 1) - 4))
+    // Narrow tile (8 slots per K-step): the 6 fragment reads go into slots 0..5, B0, B1, then A0..A3 (instruction
+    // n needs A[n/2] and B[n%2]); the loads take the odd slots of K-step 0 and every slot of K-step 3.
+#define MXFP4_FRAG_SLOT(N) (!FMT && (NJ == 4 ? ((N) & 1) == 0 : (N) < 6))
+#define MXFP4_FRAG_OF(N)                                                                       \
+    (NJ == 4 ? (((N) >> 1) < 4 ? 2 * ((N) >> 1) + 1 : 2 * (((N) >> 1) - 4)) : ((N) < 2 ? 2 * (N) + 1 : 2 * ((N)-2)))
+    // load slots of K-step 0 (second half of a stage's loads: 8, 9, ...) and of K-step 3 (first half: 0..7)
+    // (the ..._OF values are clamped to an existing load where the slot has none: the call is discarded there, but
+    // the compiler still instantiates it)
+#define MXFP4_LOAD0_SLOT(N) (((N) & 1) && 8 + ((N) >> 1) < NLOADS)
+#define MXFP4_LOAD0_OF(N) (8 + ((N) >> 1) < NLOADS ? 8 + ((N) >> 1) : 8)
+#define MXFP4_LOAD3_SLOT(N) (NJ == 4 ? ((N) & 1) : (N) < 8)
+#define MXFP4_LOAD3_OF(N) (NJ == 4 ? ((N) >> 1) : ((N) < 8 ? (N) : 0))
 #define MXFP4_16(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)
 
     // One stage = 4 K-steps of 16 matrix instructions.  Everything else is threaded between them,
@@ -410,19 +441,19 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #define MXFP4_K0(N)                                                                              \
         if (FMT && (N) < 8) read_one(buf, 2, 2, (N));                                            \
         if (MXFP4_FRAG_SLOT(N)) read_one(buf, 1, 1, MXFP4_FRAG_OF(N));                           \
-        if (MODE != 2 && ((N) & 1)) issue_load(cur, s + 1, buf ^ 1, IC<8 + ((N) >> 1)>{}, no_force{}); \
-        if (MODE == 2 && ((N) & 1)) issue_load(nxt, 0, buf ^ 1, IC<8 + ((N) >> 1)>{}, no_force{});     \
+        if constexpr (MODE != 2 && MXFP4_LOAD0_SLOT(N)) issue_load(cur, s + 1, buf ^ 1, IC<MXFP4_LOAD0_OF(N)>{}, no_force{}); \
+        if constexpr (MODE == 2 && MXFP4_LOAD0_SLOT(N)) issue_load(nxt, 0, buf ^ 1, IC<MXFP4_LOAD0_OF(N)>{}, no_force{});     \
         MXFP4_SLOT_MMA(0, N, MODE == 3) MXFP4_PIN()
         MXFP4_16(MXFP4_K0)
 #undef MXFP4_K0
 #define MXFP4_K1(N)                                                                              \
         if (FMT && (N) < 8) read_one(buf, 3, 3, (N));                                            \
         if (MXFP4_FRAG_SLOT(N)) read_one(buf, 2, 0, MXFP4_FRAG_OF(N));                           \
-        if ((MODE == 0 || MODE == 3) && (N) == 9) {                                              \
+        if ((MODE == 0 || MODE == 3) && (N) == (NJ == 4 ? 9 : 4)) {                              \
             sc_dst = scales_dst((s + 1) / BATCH + 1, (s + 1) & 3, par);                          \
             asm volatile("" : "+s"(sc_dst));                                                     \
         }                                                                                        \
-        if ((MODE == 0 || MODE == 3) && (N) == 12) {                                             \
+        if ((MODE == 0 || MODE == 3) && (N) == (NJ == 4 ? 12 : 6)) {                             \
             sc_src = scales_src(cur, (s + 1) / BATCH + 1, (s + 1) & 3);                          \
             asm volatile("" : "+s"(sc_src));                                                     \
         }                                                                                        \
@@ -430,7 +461,8 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         MXFP4_16(MXFP4_K1)
 #undef MXFP4_K1
 #define MXFP4_K2(N)                                                                              \
-        if (!FMT && (N) < 8) read_one(buf, 3, 1, (N)); /* (early: the barrier below waits for them) */ \
+        if (!FMT && NJ == 4 && (N) < 8) read_one(buf, 3, 1, (N)); /* (early: the barrier below waits for them) */ \
+        if (NJ == 2 && MXFP4_FRAG_SLOT(N)) read_one(buf, 3, 1, MXFP4_FRAG_OF(N));                \
         MXFP4_SLOT_MMA(2, N, false) MXFP4_PIN()
         MXFP4_16(MXFP4_K2)
 #undef MXFP4_K2
@@ -442,12 +474,16 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         if (FMT && MODE != 2 && (N) < 8) read_one(buf ^ 1, 0, 0, (N));                            \
         if (MODE != 2 && MXFP4_FRAG_SLOT(N)) read_one(buf ^ 1, 0, 0, MXFP4_FRAG_OF(N));           \
         if (FMT && MODE != 2 && (N) < 8) read_one(buf ^ 1, 1, 1, (N));                            \
-        if (MODE != 2 && (N) < 8) read_scale_one(s + 1, (N), par);                                \
+        if (MODE != 2 && NJ == 4 && (N) < 8) read_scale_one(s + 1, (N), par);                     \
+        if (MODE != 2 && NJ == 2 && (N) < 6) read_scale_one(s + 1, MXFP4_FRAG_OF(N), par);        \
         if ((MODE == 0 || MODE == 3) && (N) == 0) dma16(sc_dst, svoff, sc_src);                  \
-        if ((MODE == 0 || MODE == 3) && ((N) & 1)) issue_load(cur, s + 2, buf, IC<((N) >> 1)>{}, no_force{}); \
-        if (MODE != 2 && (N) == 13) __builtin_amdgcn_s_waitcnt(FMT ? 0xC07F : 0xC37F); /* lgkmcnt(0 / 3): see below */ \
-        if (MODE == 1 && ((N) & 1)) issue_load(nxt, 0, buf, IC<((N) >> 1)>{}, force_m0{});        \
-        if (MODE == 1 && !((N) & 1) && (N) < 8) issue_scales(nxt, 0, (N) >> 1, par_nxt);         \
+        if constexpr ((MODE == 0 || MODE == 3) && MXFP4_LOAD3_SLOT(N))                           \
+            issue_load(cur, s + 2, buf, IC<MXFP4_LOAD3_OF(N)>{}, no_force{});                    \
+        if (MODE != 2 && NJ == 4 && (N) == 13) __builtin_amdgcn_s_waitcnt(FMT ? 0xC07F : 0xC37F); /* lgkmcnt(0 / 3): see below */ \
+        if (MODE != 2 && NJ == 2 && (N) == 6) __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0) */ \
+        if constexpr (MODE == 1 && MXFP4_LOAD3_SLOT(N))                                          \
+            issue_load(nxt, 0, buf, IC<MXFP4_LOAD3_OF(N)>{}, force_m0{});                        \
+        if (MODE == 1 && !((N) & 1) && (N) < 2 * (NJ == 4 ? 4 : 3)) issue_scales(nxt, 0, (N) >> 1, par_nxt); \
         if (MODE == 2 && (N) == 1) issue_scales(nxt, 1, 0, par_nxt);                             \
         MXFP4_SLOT_MMA(3, N, false) MXFP4_PIN()
         MXFP4_16(MXFP4_K3)
@@ -465,11 +501,11 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // ---- first tile: fill the pipeline --------------------------------------------------------
     // all of stage 0, the first 8 loads of stage 1, scale batch 0 and the first load of batch 1
     TileSrc cur = tile_src(lw);
-#define MXFP4_FILL(N) issue_load(cur, 0, 0, IC<(N)>{}, no_force{});
+#define MXFP4_FILL(N) if constexpr ((N) < NLOADS) issue_load(cur, 0, 0, IC<((N) < NLOADS ? (N) : 0)>{}, no_force{});
     MXFP4_16(MXFP4_FILL)
 #undef MXFP4_FILL
 #pragma unroll
-    for (int j = 0; j < 4; ++j) issue_scales(cur, 0, j, 0);
+    for (int j = 0; j < (NJ == 4 ? 4 : 3); ++j) issue_scales(cur, 0, j, 0);
     issue_scales(cur, 1, 0, 0);
     int par = 0;
     const int b_last = (nstages - 1) / BATCH;
@@ -483,11 +519,12 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         // here); after the barrier start stage 1's first half and fetch the first fragments
         if (lloc == lw) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");  // (later tiles waited before the epilogue)
         __syncthreads();
-#define MXFP4_FILL(N) if ((N) < 8) issue_load(cur, 1, bp ^ 1, IC<((N) & 7)>{}, no_force{});
+#define MXFP4_FILL(N) if constexpr ((N) < 8) issue_load(cur, 1, bp ^ 1, IC<((N) & 7)>{}, no_force{});
         MXFP4_16(MXFP4_FILL)
 #undef MXFP4_FILL
 #pragma unroll
         for (int f = 0; f < 8; ++f) {
+            if ((f & 1) && (f >> 1) >= NJ) continue;  // (narrow tile: two B fragments only)
             read_one(bp, 0, 0, f);
             if (FMT) read_one(bp, 1, 1, f);
             read_scale_one(0, f, par);
@@ -516,8 +553,82 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
         // halves swap when r & 16), which keeps both the 8/16-byte writes and the 16-byte reads
         // conflict-free.
         uint8_t *epi = smem + ((((nstages - 1) & 1) ^ bp) ? STAGE_BYTES : 0) + wave * 16384;
-        const int64_t row0 = cur.m0 + wm * 128, col0 = cur.n0 + wn * 128;
-        if (!OUT_FP32) {
+        const int64_t row0 = cur.m0 + wm * 128, col0 = cur.n0 + wn * (32 * NJ);
+        if constexpr (NJ == 2 && !OUT_FP32) {
+            // Narrow tile, bf16: the wave's 128 rows x 64 columns are 16 KiB, one pass.  A row is 8 chunks of 16
+            // bytes; chunk c of row r sits at position c ^ ((r >> 1) & 7): the 8-byte writes of a quarter wave
+            // (16 rows, one chunk) and the 16-byte reads (2 rows x 8 chunks) then cover all banks evenly.
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        const int r = i * 32 + fr, c = j * 4 + qd;
+                        uint2 pk;
+                        pk.x = pack_bf16(acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1]);
+                        pk.y = pack_bf16(acc[i][j][4 * qd + 2], acc[i][j][4 * qd + 3]);
+                        *reinterpret_cast<uint2 *>(epi + r * 128 + ((c ^ ((r >> 1) & 7)) << 4) + (fh << 3)) = pk;
+                        if (qd == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+            // 8 lanes x 16 bytes = one 128-byte row segment; 8 rows per instruction
+            const int rl = lane >> 3, ch = lane & 7;
+            uint16_t *obase = reinterpret_cast<uint16_t *>(out) + (row0 + rl) * ld + col0 + ch * 8;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                v4i buf[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int r = (8 * h + u) * 8 + rl;
+                    buf[u] = *reinterpret_cast<const v4i *>(epi + r * 128 + ((ch ^ ((r >> 1) & 7)) << 4));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    __builtin_nontemporal_store(buf[u], reinterpret_cast<v4i *>(obase + (int64_t)((8 * h + u) * 8) * ld));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else if constexpr (NJ == 2) {
+            // Narrow tile, fp32: 128 rows x 256 bytes in two passes of 64 rows; chunk c (4 columns) of row r at
+            // position c ^ (r & 15)
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+                for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int qd = 0; qd < 4; ++qd) {
+                            const int i = 2 * pass + ii;
+                            const int r = ii * 32 + fr, c = j * 8 + qd * 2 + fh;
+                            *reinterpret_cast<v4f *>(epi + r * 256 + ((c ^ (r & 15)) << 4)) =
+                                (v4f){acc[i][j][4 * qd + 0], acc[i][j][4 * qd + 1], acc[i][j][4 * qd + 2],
+                                      acc[i][j][4 * qd + 3]};
+                            if (qd == 3) __builtin_amdgcn_sched_barrier(0);
+                        }
+                // 16 lanes x 16 bytes = one 256-byte row segment; 4 rows per instruction
+                const int rl = lane >> 4, ch = lane & 15;
+                float *obase = reinterpret_cast<float *>(out) + (row0 + pass * 64 + rl) * ld + col0 + ch * 4;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    v4f buf[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int r = (8 * h + u) * 4 + rl;
+                        buf[u] = *reinterpret_cast<const v4f *>(epi + r * 256 + ((ch ^ (r & 15)) << 4));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        v4f *o = reinterpret_cast<v4f *>(obase + (int64_t)((8 * h + u) * 4) * ld);
+                        v4f v = buf[u];
+                        if (ACC) v += *o;
+                        __builtin_nontemporal_store(v, o);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else if constexpr (!OUT_FP32) {
 #pragma unroll
             for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
@@ -612,6 +723,12 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #undef MXFP4_SLOT_MMA
 #undef MXFP4_PIN
 #undef MXFP4_16
+#undef MXFP4_FRAG_SLOT
+#undef MXFP4_FRAG_OF
+#undef MXFP4_LOAD0_SLOT
+#undef MXFP4_LOAD0_OF
+#undef MXFP4_LOAD3_SLOT
+#undef MXFP4_LOAD3_OF
 }
 
 struct TileGemm {
@@ -622,13 +739,13 @@ struct TileGemm {
     int tiles_m, tiles_n;
 };
 
-template <bool OUT_FP32, bool ACC, int FMT>
+template <bool OUT_FP32, bool ACC, int FMT, int NJ>
 __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const TileGemm p)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
-    gemm_tile_body<OUT_FP32, ACC, FMT>(p.aq, p.as, p.bq, p.bs, p.C, p.out, p.ld, p.tiles_m, p.tiles_n, blockIdx.x,
-                                  gridDim.x, smem, lds0);
+    gemm_tile_body<OUT_FP32, ACC, FMT, NJ>(p.aq, p.as, p.bq, p.bs, p.C, p.out, p.ld, p.tiles_m, p.tiles_n,
+                                           blockIdx.x, gridDim.x, smem, lds0);
 }
 
 // Two independent GEMMs in one launch of 256 workgroups (Dgrad and Wgrad of one layer): on every XCD the
@@ -644,10 +761,10 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const uint32_t xcd = blockIdx.x & 7, lw = blockIdx.x >> 3;
     if (lw < (uint32_t)n0)
-        gemm_tile_body<OUT0, false, 0>(p0.aq, p0.as, p0.bq, p0.bs, p0.C, p0.out, p0.ld, p0.tiles_m, p0.tiles_n,
+        gemm_tile_body<OUT0, false, 0, 4>(p0.aq, p0.as, p0.bq, p0.bs, p0.C, p0.out, p0.ld, p0.tiles_m, p0.tiles_n,
                                     lw * 8 + xcd, (uint32_t)n0 * 8, smem, lds0);
     else
-        gemm_tile_body<OUT1, ACC1, 0>(p1.aq, p1.as, p1.bq, p1.bs, p1.C, p1.out, p1.ld, p1.tiles_m, p1.tiles_n,
+        gemm_tile_body<OUT1, ACC1, 0, 4>(p1.aq, p1.as, p1.bq, p1.bs, p1.C, p1.out, p1.ld, p1.tiles_m, p1.tiles_n,
                                    (lw - n0) * 8 + xcd, (uint32_t)(32 - n0) * 8, smem, lds0);
 }
 
@@ -670,18 +787,20 @@ static int device_cus()
 // the tiled kernel wants whole 256 x 256 tiles, K in whole stages (128 bytes of codes per row: 256 E2M1
 // or 128 E4M3 elements) and at least 1024 (scale bytes are fetched 32 per row), and 16-byte aligned
 // code rows and output rows
-static bool tile_eligible(const GemmArgs &g)
+// (tile_n: 256, or 128 for the narrow tile, which exists for E2M1 operands only)
+static bool tile_eligible(const GemmArgs &g, int tile_n = TILE)
 {
     if (g.a_fmt != g.b_fmt) return false;  // mixed formats: any-shape kernel
+    if (tile_n != TILE && g.a_fmt != 0) return false;
     const bool k_ok = g.C >= 1024 && (g.C % (g.a_fmt ? 128 : 256)) == 0;
-    return k_ok && (g.Ra % TILE) == 0 && (g.Rb % TILE) == 0 && (g.ld % 8) == 0 &&
+    return k_ok && (g.Ra % TILE) == 0 && (g.Rb % tile_n) == 0 && (g.ld % 8) == 0 &&
            (reinterpret_cast<uintptr_t>(g.as) % 16) == 0 && (reinterpret_cast<uintptr_t>(g.bs) % 16) == 0 &&
            (g.Ra / TILE) * (g.Rb / TILE) < (1 << 30) && g.C < (int64_t(1) << 26);  // (64 code rows: 32-bit lane offsets)
 }
 
-static TileGemm tile_args(const GemmArgs &g)
+static TileGemm tile_args(const GemmArgs &g, int tile_n = TILE)
 {
-    return TileGemm{g.aq, g.as, g.bq, g.bs, g.C, g.out, g.ld, (int)(g.Ra / TILE), (int)(g.Rb / TILE)};
+    return TileGemm{g.aq, g.as, g.bq, g.bs, g.C, g.out, g.ld, (int)(g.Ra / TILE), (int)(g.Rb / tile_n)};
 }
 
 template <int AF, int BF>
@@ -708,30 +827,6 @@ static hipError_t launch_any(const GemmArgs &g, hipStream_t st)
     return g.b_fmt == 0 ? launch_any_f<1, 0>(g, st) : launch_any_f<1, 1>(g, st);
 }
 
-template <int FMT>
-static hipError_t launch_tiled_f(const GemmArgs &g, hipStream_t st)
-{
-    const TileGemm p = tile_args(g);
-    // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
-    const int T = p.tiles_m * p.tiles_n;
-    const int cus = device_cus();
-    dim3 grid((unsigned)(T < cus ? T : cus));
-    if (g.out_fp32) {
-        if (g.accumulate)
-            hipLaunchKernelGGL((gemm_tile_kernel<true, true, FMT>), grid, dim3(256), 0, st, p);
-        else
-            hipLaunchKernelGGL((gemm_tile_kernel<true, false, FMT>), grid, dim3(256), 0, st, p);
-    } else {
-        hipLaunchKernelGGL((gemm_tile_kernel<false, false, FMT>), grid, dim3(256), 0, st, p);
-    }
-    return hipGetLastError();
-}
-
-static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
-{
-    return g.a_fmt ? launch_tiled_f<1>(g, st) : launch_tiled_f<0>(g, st);
-}
-
 // rows r0.. (n of them) of A and columns c0.. (m of them) of B: the same problem on a sub-block of the output
 static GemmArgs sub_block(const GemmArgs &g, int64_t r0, int64_t n, int64_t c0, int64_t m)
 {
@@ -747,9 +842,51 @@ static GemmArgs sub_block(const GemmArgs &g, int64_t r0, int64_t n, int64_t c0, 
     return h;
 }
 
+template <int FMT, int NJ>
+static hipError_t launch_tiled_f(const GemmArgs &g, hipStream_t st)
+{
+    const TileGemm p = tile_args(g, 64 * NJ);
+    // persistent: one workgroup per CU (the kernel takes all of a CU's LDS) walks several tiles
+    const int T = p.tiles_m * p.tiles_n;
+    const int cus = device_cus();
+    dim3 grid((unsigned)(T < cus ? T : cus));
+    if (g.out_fp32) {
+        if (g.accumulate)
+            hipLaunchKernelGGL((gemm_tile_kernel<true, true, FMT, NJ>), grid, dim3(256), 0, st, p);
+        else
+            hipLaunchKernelGGL((gemm_tile_kernel<true, false, FMT, NJ>), grid, dim3(256), 0, st, p);
+    } else {
+        hipLaunchKernelGGL((gemm_tile_kernel<false, false, FMT, NJ>), grid, dim3(256), 0, st, p);
+    }
+    return hipGetLastError();
+}
+
+// Whole tiles only.  256 x 256 tiles, except where they would leave compute units idle (E2M1 operands):
+//   * fewer tiles than compute units: 256 x 128 tiles (twice as many);
+//   * a last round of tiles at most half full (and at most three rounds in all): the tile rows that make up whole
+//     rounds run on 256 x 256 tiles, the remaining tile rows on 256 x 128 tiles in a second launch.
+static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
+{
+    if (g.a_fmt) return launch_tiled_f<1, 4>(g, st);
+    const int64_t tiles_m = g.Ra / TILE, tiles_n = g.Rb / TILE, T = tiles_m * tiles_n;
+    const int64_t cus = device_cus();
+    if (T < cus) return launch_tiled_f<0, 2>(g, st);
+    const int64_t rounds = T / cus, rem = T % cus;
+    if (rem != 0 && 2 * rem <= cus && rounds <= 2) {
+        const int64_t m_main = rounds * cus / tiles_n;  // tile rows that fit into the whole rounds
+        if (m_main >= 1 && m_main < tiles_m) {
+            hipError_t e = launch_tiled_f<0, 4>(sub_block(g, 0, m_main * TILE, 0, g.Rb), st);
+            if (e != hipSuccess) return e;
+            return launch_tiled_f<0, 2>(sub_block(g, m_main * TILE, g.Ra - m_main * TILE, 0, g.Rb), st);
+        }
+    }
+    return launch_tiled_f<0, 4>(g, st);
+}
+
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
 {
     if (tile_eligible(g)) return launch_tiled(g, st);
+    if (tile_eligible(g, TILE / 2)) return launch_tiled_f<0, 2>(g, st);  // (columns in whole 128s but not 256s)
     // Ragged row counts: the 256-aligned interior goes through the tiled kernel, the right and bottom edge
     // strips (less than one tile wide) through the any-shape kernel.
     const int64_t ra = g.Ra / TILE * TILE, rb = g.Rb / TILE * TILE;

@@ -257,6 +257,47 @@ def test_many_tiles_per_workgroup_whole_output(C):
     assert torch.equal(acc, f32 + f32)                # the accumulating epilogue, everywhere
 
 
+@pytest.mark.parametrize("shape", [(256 * 17, 128 * 17, 1280), (256 * 9, 128 * 35, 1024), (1024, 4096, 2048),
+                                   (8192, 1024, 1024)])
+def test_narrow_tiles_whole_output(shape):
+    # outputs whose column count is a whole number of 128s but not of 256s, or that have fewer 256 x 256 tiles than
+    # the chip has compute units, run on 256 x 128 tiles; with 289 and 315 of them a workgroup hands over from tile
+    # to tile (odd and even numbers of K stages).  Every element, fp32, bf16 and accumulating.
+    Ra, Rb, C = shape
+    rng = np.random.default_rng(Ra + Rb + C)
+    aq, as_ = rand_operand(rng, Ra, C)
+    bq, bs = rand_operand(rng, Rb, C)
+    want, absum = oracle.gemm(aq, as_, bq, bs)
+    ga, gas, gb, gbs = gpu(aq), gpu(as_), gpu(bq), gpu(bs)
+    canvas = torch.full((Ra + 1, Rb + 8), 7.0, dtype=torch.float32, device="cuda:0")
+    mx.mxfp4_gemm(ga, gas, gb, gbs, out=canvas[:Ra, :Rb], out_dtype=mx.OUT_FP32)
+    b16 = mx.mxfp4_gemm(ga, gas, gb, gbs, out_dtype=mx.OUT_BF16)
+    torch.cuda.synchronize()
+    c = canvas.cpu().numpy()
+    assert_close(c[:Ra, :Rb], want, absum)
+    assert np.all(c[:Ra, Rb:] == 7.0) and np.all(c[Ra] == 7.0)          # nothing written outside
+    f32 = canvas[:Ra, :Rb].clone()
+    assert torch.equal(b16, f32.to(torch.bfloat16))
+    mx.mxfp4_gemm(ga, gas, gb, gbs, out=canvas[:Ra, :Rb], out_dtype=mx.OUT_FP32, accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.equal(canvas[:Ra, :Rb], f32 + f32)
+
+
+@pytest.mark.parametrize("shape", [(6144, 4096, 2048), (256 * 40, 256 * 8, 1024)])
+def test_part_filled_last_round_runs_on_narrow_tiles(shape):
+    # 384 and 320 tiles of 256 x 256 on 256 compute units: the tile rows of the whole round(s) run on 256 x 256
+    # tiles, the rest on 256 x 128 tiles in a second launch; every element of the output against the oracle
+    Ra, Rb, C = shape
+    rng = np.random.default_rng(Ra * 3 + Rb + C)
+    aq, as_ = rand_operand(rng, Ra, C)
+    bq, bs = rand_operand(rng, Rb, C)
+    want, absum = oracle.gemm(aq, as_, bq, bs)
+    f32 = run_gemm(aq, as_, bq, bs, out_dtype=mx.OUT_FP32)
+    b16 = run_gemm(aq, as_, bq, bs, out_dtype=mx.OUT_BF16)
+    assert_close(f32.cpu().numpy(), want, absum)
+    assert torch.equal(b16, f32.to(torch.bfloat16))
+
+
 def test_config2_shape_every_tile():
     # 8192 x 6144 x 4096 (fused QKV Fprop) through the two single-operation calls: complete K-sums at a patch
     # inside every output tile, whole rows and whole columns (tests/test_gpu_configs.py compares the whole output)

@@ -40,7 +40,7 @@ BYTES_PER_ELEM_DUAL = 2.0 + 2 * (0.5 + 1.0 / 32.0)  # one read, both quantisatio
 # Bytes crossing the L2's outward port per GEMM launch (mean of the three GEMMs of a step): not measured in this
 # run but taken from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in the file named below (FETCH_SIZE
 # x 2.0 after calibration against a 256 MiB copy).  They include what the 256 MB Infinity Cache serves.
-GEMM_TRAFFIC_BYTES = 290.8e6
+GEMM_TRAFFIC_BYTES = 290.1e6
 GEMM_TRAFFIC_SOURCE = "profiles/qkv_traffic_counters.md"
 # operands once + output once, mean of Fprop (bf16 out), Dgrad (bf16 out), Wgrad (fp32 out)
 GEMM_ALGORITHMIC_BYTES = ((M * K + N * K) * 0.53125 + M * N * 2 + (M * N + K * N) * 0.53125 + M * K * 2 +

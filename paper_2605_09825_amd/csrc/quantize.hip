@@ -212,13 +212,14 @@ __device__ __forceinline__ void widen(const uint4 (&raw)[4], float (&v)[32])
 
 // ---- row-wise (1x32) ---------------------------------------------------------------------
 // One lane per block.  nblocks = rows * (cols/32); block g is row g / bpr, column block g % bpr.
-template <int HAD, int RND>
+// STREAM: tensor larger than the last-level cache: non-temporal code stores.
+template <int HAD, int RND, int STREAM>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t nblocks,
                                                             int64_t bpr, int64_t ld, int dense,
                                                             uint32_t sign_mask, RngKey key,
-                                                            uint8_t *__restrict__ q, uint8_t *__restrict__ s,
-                                                            int streaming)
+                                                            uint8_t *__restrict__ q, uint8_t *__restrict__ s)
 {
+    constexpr int streaming = STREAM;
     int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (g >= nblocks) return;
     const uint16_t *src;
@@ -229,7 +230,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
         src = x + row * ld + (g - row * bpr) * 32;
     }
     const uint4 *p = reinterpret_cast<const uint4 *>(src);
-    uint4 raw[4];
+    uint4 raw[4];  // (plain loads also for tensors beyond the cache: non-temporal 16-byte loads measured 30 % slower
+                   // here, whereas the column-wise kernel's dword loads gain 8 % from the hint)
 #pragma unroll
     for (int j = 0; j < 4; ++j) raw[j] = p[j];
     float v[32];
@@ -283,7 +285,10 @@ struct TileJob {
     RngKey key, key_row;  // stochastic-rounding streams of the column-wise and of the row-wise output
 };
 
-template <int HAD, int RND, int MODE>
+// STREAM: the tensor is larger than the last-level cache: it is read with non-temporal loads and its codes are
+// written with non-temporal stores (a compile-time choice: as a run-time branch around the loads the compiler
+// merges the two sides and the hint is lost).
+template <int HAD, int RND, int MODE, int STREAM>
 __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, const TileJob job1,
                                                             uint32_t sign_mask)
 {
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     const uint32_t nb = second ? job1.nblocks : job0.nblocks;
     const uint32_t band_rows = second ? job1.band_rows : job0.band_rows;
     const int s_vec8 = second ? job1.s_vec8 : job0.s_vec8, s_row_vec4 = second ? job1.s_row_vec4 : job0.s_row_vec4;
-    const int streaming = second ? job1.streaming : job0.streaming;
+    constexpr int streaming = STREAM;
     const RngKey key = second ? job1.key : job0.key, key_row = second ? job1.key_row : job0.key_row;
     const uint32_t bid = blockIdx.x - (second ? job0.nblocks : 0u);
 
@@ -349,8 +354,14 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     uint32_t raw[32];
     if (active) {
         const uint16_t *p = x + (rb * 32) * ld + col;
+        if constexpr (STREAM) {  // read once: keep it out of the way of the output in the caches
 #pragma unroll
-        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint32_t *>(p + i * ld);
+            for (int i = 0; i < 32; ++i)
+                raw[i] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p + i * ld));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint32_t *>(p + i * ld);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < 32; ++i) raw[i] = 0;
@@ -621,12 +632,15 @@ hipError_t launch_rows_h(const QuantArgs &a, hipStream_t st)
     const uint32_t sign_mask = sign_mask_of(a.seed);
     const int dense = (a.ld == a.cols);
     const int streaming = a.rows * a.cols * 2 > LLC_BYTES;
-    if (a.rounding == RND_RNE)
-        hipLaunchKernelGGL((quantize_rows_kernel<HAD, RND_RNE>), dim3(grid), dim3(256), 0, st, a.x, nblocks, bpr,
-                           a.ld, dense, sign_mask, key, a.q, a.s, streaming);
-    else
-        hipLaunchKernelGGL((quantize_rows_kernel<HAD, RND_SR>), dim3(grid), dim3(256), 0, st, a.x, nblocks, bpr,
-                           a.ld, dense, sign_mask, key, a.q, a.s, streaming);
+#define MXFP4_LAUNCH_ROWS(R, S)                                                                              \
+    hipLaunchKernelGGL((quantize_rows_kernel<HAD, R, S>), dim3(grid), dim3(256), 0, st, a.x, nblocks, bpr, a.ld, \
+                       dense, sign_mask, key, a.q, a.s)
+    if (a.rounding == RND_RNE) {
+        if (streaming) MXFP4_LAUNCH_ROWS(RND_RNE, 1); else MXFP4_LAUNCH_ROWS(RND_RNE, 0);
+    } else {
+        if (streaming) MXFP4_LAUNCH_ROWS(RND_SR, 1); else MXFP4_LAUNCH_ROWS(RND_SR, 0);
+    }
+#undef MXFP4_LAUNCH_ROWS
     return hipGetLastError();
 }
 
@@ -660,10 +674,15 @@ hipError_t launch_cols_h(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
     if (b) j1 = make_job<MODE>(*b);
     dim3 grid(j0.nblocks + j1.nblocks);
     const uint32_t sign_mask = sign_mask_of(a.seed);
-    if (a.rounding == RND_RNE)
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_RNE, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask);
-    else
-        hipLaunchKernelGGL((quantize_cols_kernel<HAD, RND_SR, MODE>), grid, dim3(512), 0, st, j0, j1, sign_mask);
+    const bool streaming = j0.streaming && (!b || j1.streaming);  // (two tensors in one launch: only if both want it)
+#define MXFP4_LAUNCH_COLS(R, S) \
+    hipLaunchKernelGGL((quantize_cols_kernel<HAD, R, MODE, S>), grid, dim3(512), 0, st, j0, j1, sign_mask)
+    if (a.rounding == RND_RNE) {
+        if (streaming) MXFP4_LAUNCH_COLS(RND_RNE, 1); else MXFP4_LAUNCH_COLS(RND_RNE, 0);
+    } else {
+        if (streaming) MXFP4_LAUNCH_COLS(RND_SR, 1); else MXFP4_LAUNCH_COLS(RND_SR, 0);
+    }
+#undef MXFP4_LAUNCH_COLS
     return hipGetLastError();
 }
 

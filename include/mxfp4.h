@@ -196,6 +196,19 @@ int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_
                int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream);
 
 /*
+ * Which kernels mxfp4_gemm_fmt cuts a product of this shape into on a device with `compute_units` compute
+ * units (256 on MI355X), for operands and an output aligned as those calls demand: the tiled kernel of the
+ * block-scaled FP4 GEMM (Sec. 2.1) on 256 x 256 tiles or, where those would leave compute units idle, on
+ * 256 x 128 tiles, and a slower any-shape kernel for edge strips and for contraction lengths below 1024 or
+ * not in whole 256s (MXFP8: 128s).  Host-only: touches no device.
+ *   parts[5 * i ..] = kind (0 any-shape, 1 tiled 256 x 256, 2 tiled 256 x 128), first row, rows, first column,
+ *   columns of block i of the output; *n_parts <= 4 receives their number (0 for an empty product).
+ * Returns MXFP4_OK, MXFP4_EINVAL or MXFP4_ESHAPE as the GEMM call would.
+ */
+int mxfp4_gemm_plan(int64_t R_a, int64_t R_b, int64_t C, int a_format, int b_format, int64_t ld_out,
+                    int compute_units, int *n_parts, int64_t parts[20]);
+
+/*
  * Fprop of one linear layer (App. C.1): Y[M][N] = Q(X H) Q(W H)^T, contraction over K.
  *   x bf16 [M][K], w bf16 [N][K] (both dense: ld = K), y [M][N] dense, dtype cfg->y_dtype
  *   workspace: device scratch of at least mxfp4_linear_workspace_bytes(M,N,K,cfg,0) bytes,

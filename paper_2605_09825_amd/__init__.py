@@ -26,7 +26,7 @@ GEOM_1D, GEOM_2D = 0, 1
 FMT_E2M1, FMT_E4M3 = 0, 1
 
 EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_quantize_fp8", "mxfp4_gemm",
-           "mxfp4_gemm_fmt", "mxfp4_linear_fwd", "mxfp4_linear_fwd_static", "mxfp4_linear_bwd",
+           "mxfp4_gemm_fmt", "mxfp4_gemm_plan", "mxfp4_linear_fwd", "mxfp4_linear_fwd_static", "mxfp4_linear_bwd",
            "mxfp4_linear_fwd_save", "mxfp4_linear_bwd_saved", "mxfp4_linear_saved_bytes",
            "mxfp4_linear_saved_layout", "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout",
            "mxfp4_status_string")
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
         L.mxfp4_linear_fwd.restype = ci
         L.mxfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
+        L.mxfp4_gemm_plan.restype = ci
+        L.mxfp4_gemm_plan.argtypes = [i64, i64, i64, ci, ci, i64, ci, ctypes.POINTER(ci), ctypes.POINTER(i64)]
         L.mxfp4_linear_fwd_static.restype = ci
         L.mxfp4_linear_fwd_static.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp]
         L.mxfp4_linear_bwd.restype = ci
@@ -209,6 +211,19 @@ def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumula
                                                       Ra, Rb, C, _ptr(out), ld, out_dtype, int(accumulate),
                                                       _stream_ptr(stream)))
     return out
+
+
+GEMM_ANY, GEMM_TILED_256, GEMM_TILED_128 = 0, 1, 2
+
+
+def mxfp4_gemm_plan(Ra: int, Rb: int, C: int, a_format: int = FMT_E2M1, b_format: int = FMT_E2M1,
+                    ld_out: Optional[int] = None, compute_units: int = 256):
+    """The kernels a GEMM of this shape is cut into: list of (kind, r0, rows, c0, cols).  Host-only."""
+    n = ctypes.c_int(0)
+    parts = (ctypes.c_int64 * 20)()
+    _check("mxfp4_gemm_plan", lib().mxfp4_gemm_plan(Ra, Rb, C, a_format, b_format, Rb if ld_out is None else ld_out,
+                                                    compute_units, ctypes.byref(n), parts))
+    return [tuple(int(parts[5 * i + k]) for k in range(5)) for i in range(n.value)]
 
 
 def mxfp4_linear_workspace_bytes(M: int, N: int, K: int, cfg: LinearCfg, bwd: bool) -> int:

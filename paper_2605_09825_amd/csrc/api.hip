@@ -292,6 +292,28 @@ int mxfp4_gemm_fmt(const void *a_q, const void *a_s, int a_format, const void *b
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
+int mxfp4_gemm_plan(int64_t R_a, int64_t R_b, int64_t C, int a_format, int b_format, int64_t ld_out,
+                    int compute_units, int *n_parts, int64_t parts[20])
+{
+    if (!n_parts || !parts || compute_units <= 0) return MXFP4_EINVAL;
+    if ((a_format != MXFP4_FMT_E2M1 && a_format != MXFP4_FMT_E4M3) ||
+        (b_format != MXFP4_FMT_E2M1 && b_format != MXFP4_FMT_E4M3))
+        return MXFP4_EINVAL;
+    if (R_a < 0 || R_b < 0 || C < 0 || (C % 32) != 0 || ld_out < R_b) return MXFP4_ESHAPE;
+    *n_parts = 0;
+    if (R_a == 0 || R_b == 0) return MXFP4_OK;
+    // (operand pointers as well aligned as the call itself demands; the plan depends on them no further)
+    const GemmArgs g{nullptr, nullptr, nullptr, nullptr, R_a, R_b, C, nullptr, ld_out, 1, 0, a_format, b_format};
+    const GemmPlan plan = plan_gemm(g, compute_units);
+    for (int i = 0; i < plan.n; ++i) {
+        const GemmPart &p = plan.part[i];
+        const int64_t row[5] = {p.kind, p.r0, p.rows, p.c0, p.cols};
+        memcpy(parts + 5 * i, row, sizeof(row));
+    }
+    *n_parts = plan.n;
+    return MXFP4_OK;
+}
+
 int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_s, int64_t R_a, int64_t R_b,
                int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream)
 {

@@ -137,7 +137,8 @@ __global__ __launch_bounds__(256) void gemm_any_kernel(const uint8_t *__restrict
 
 // ---- tiled kernel: 256 x 256 output tile per workgroup, K consumed in stages of 256 ---------
 // 4 waves (2 x 2), each a 128 x 128 sub-tile = 4 x 4 tiles of V_MFMA_SCALE_F32_32X32X64_F8F6F4
-// (256 accumulator registers per lane).  With FP4 operands that instruction takes, per lane l,
+// (256 accumulator registers per lane); a narrow variant works on 256 x 128 tiles (sub-tile 128 x 64, 4 x 2
+// instruction tiles) with the same data path, see gemm_tile_body.  With FP4 operands that instruction takes, per lane l,
 // the 32 K-elements 32*(l/32).. of row l%32 of each operand (one MX block, 16 bytes) and the
 // block's scale byte; the result holds, in register e of lane l, D[8*(e/4) + 4*(l/32) + e%4][l%32].
 //
@@ -414,7 +415,7 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
 #define MXFP4_LOAD3_OF(N) (NJ == 4 ? ((N) >> 1) : ((N) < 8 ? (N) : 0))
 #define MXFP4_16(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)
 
-    // One stage = 4 K-steps of 16 matrix instructions.  Everything else is threaded between them,
+    // One stage = 4 K-steps of 16 (narrow tile: 8) matrix instructions.  Everything else is threaded between them,
     // one item per matrix instruction, and pinned there with scheduling barriers: with a single
     // wave per SIMD any stall of the wave (a burst of loads filling the memory pipeline's queue,
     // a late fragment) idles the matrix unit, so loads are issued a few at a time.
@@ -861,51 +862,70 @@ static hipError_t launch_tiled_f(const GemmArgs &g, hipStream_t st)
     return hipGetLastError();
 }
 
-// Whole tiles only.  256 x 256 tiles, except where they would leave compute units idle (E2M1 operands):
+// Which kernels a GEMM is cut into (host logic only: no device is touched; cus = compute units of the device).
+// Whole 256 x 256 tiles run on the tiled kernel, except where that would leave compute units idle (E2M1 operands):
 //   * fewer tiles than compute units: 256 x 128 tiles (twice as many);
 //   * a last round of tiles at most half full (and at most three rounds in all): the tile rows that make up whole
-//     rounds run on 256 x 256 tiles, the remaining tile rows on 256 x 128 tiles in a second launch.
-static hipError_t launch_tiled(const GemmArgs &g, hipStream_t st)
+//     rounds run on 256 x 256 tiles, the remaining tile rows on 256 x 128 tiles in a second launch;
+//   * a column count in whole 128s but not 256s: 256 x 128 tiles throughout.
+// Ragged row or column counts: the 256-aligned interior as above, the right and bottom edge strips (less than one
+// tile wide) on the any-shape kernel; everything else on the any-shape kernel.
+static void plan_tiled(const GemmArgs &g, int64_t r0, int64_t rows, int64_t cols, int64_t cus, GemmPlan &plan)
 {
-    if (g.a_fmt) return launch_tiled_f<1, 4>(g, st);
-    const int64_t tiles_m = g.Ra / TILE, tiles_n = g.Rb / TILE, T = tiles_m * tiles_n;
-    const int64_t cus = device_cus();
-    if (T < cus) return launch_tiled_f<0, 2>(g, st);
+    auto add = [&](int kind, int64_t rr0, int64_t rr) { plan.part[plan.n++] = GemmPart{kind, rr0, rr, 0, cols}; };
+    if (g.a_fmt) return add(GEMM_TILED_256, r0, rows);
+    const int64_t tiles_m = rows / TILE, tiles_n = cols / TILE, T = tiles_m * tiles_n;
+    if (T < cus) return add(GEMM_TILED_128, r0, rows);
     const int64_t rounds = T / cus, rem = T % cus;
     if (rem != 0 && 2 * rem <= cus && rounds <= 2) {
         const int64_t m_main = rounds * cus / tiles_n;  // tile rows that fit into the whole rounds
         if (m_main >= 1 && m_main < tiles_m) {
-            hipError_t e = launch_tiled_f<0, 4>(sub_block(g, 0, m_main * TILE, 0, g.Rb), st);
-            if (e != hipSuccess) return e;
-            return launch_tiled_f<0, 2>(sub_block(g, m_main * TILE, g.Ra - m_main * TILE, 0, g.Rb), st);
+            add(GEMM_TILED_256, r0, m_main * TILE);
+            return add(GEMM_TILED_128, r0 + m_main * TILE, rows - m_main * TILE);
         }
     }
-    return launch_tiled_f<0, 4>(g, st);
+    add(GEMM_TILED_256, r0, rows);
+}
+
+GemmPlan plan_gemm(const GemmArgs &g, int cus)
+{
+    GemmPlan plan;
+    plan.n = 0;
+    if (tile_eligible(g)) {
+        plan_tiled(g, 0, g.Ra, g.Rb, cus, plan);
+    } else if (tile_eligible(g, TILE / 2)) {
+        plan.part[plan.n++] = GemmPart{GEMM_TILED_128, 0, g.Ra, 0, g.Rb};
+    } else {
+        const int64_t ra = g.Ra / TILE * TILE, rb = g.Rb / TILE * TILE;
+        // (the interior starts at offset 0 of every array, so it keeps the alignment of the whole problem; the
+        // any-shape kernel asks none of the strips' output pointers)
+        if (ra > 0 && rb > 0 && tile_eligible(sub_block(g, 0, ra, 0, rb))) {
+            plan_tiled(g, 0, ra, rb, cus, plan);
+            if (g.Rb > rb) plan.part[plan.n++] = GemmPart{GEMM_ANY, 0, g.Ra, rb, g.Rb - rb};
+            if (g.Ra > ra) plan.part[plan.n++] = GemmPart{GEMM_ANY, ra, g.Ra - ra, 0, rb};
+        } else {
+            plan.part[plan.n++] = GemmPart{GEMM_ANY, 0, g.Ra, 0, g.Rb};
+        }
+    }
+    return plan;
 }
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
 {
-    if (tile_eligible(g)) return launch_tiled(g, st);
-    if (tile_eligible(g, TILE / 2)) return launch_tiled_f<0, 2>(g, st);  // (columns in whole 128s but not 256s)
-    // Ragged row counts: the 256-aligned interior goes through the tiled kernel, the right and bottom edge
-    // strips (less than one tile wide) through the any-shape kernel.
-    const int64_t ra = g.Ra / TILE * TILE, rb = g.Rb / TILE * TILE;
-    if (ra > 0 && rb > 0) {
-        const GemmArgs interior = sub_block(g, 0, ra, 0, rb);
-        // (the interior starts at offset 0 of every array, so it keeps the alignment of the whole problem; the
-        // any-shape kernel asks none of the strips' output pointers)
-        if (tile_eligible(interior)) {
-            hipError_t e = launch_tiled(interior, st);
-            if (e != hipSuccess) return e;
-            if (g.Rb > rb) {
-                e = launch_any(sub_block(g, 0, g.Ra, rb, g.Rb - rb), st);
-                if (e != hipSuccess) return e;
-            }
-            if (g.Ra > ra) e = launch_any(sub_block(g, ra, g.Ra - ra, 0, rb), st);
-            return e;
-        }
+    const GemmPlan plan = plan_gemm(g, device_cus());
+    for (int i = 0; i < plan.n; ++i) {
+        const GemmPart &p = plan.part[i];
+        const GemmArgs h = sub_block(g, p.r0, p.rows, p.c0, p.cols);
+        hipError_t e;
+        if (p.kind == GEMM_ANY)
+            e = launch_any(h, st);
+        else if (p.kind == GEMM_TILED_128)
+            e = launch_tiled_f<0, 2>(h, st);
+        else
+            e = g.a_fmt ? launch_tiled_f<1, 4>(h, st) : launch_tiled_f<0, 4>(h, st);
+        if (e != hipSuccess) return e;
     }
-    return launch_any(g, st);
+    return hipSuccess;
 }
 
 // g0 (no accumulation) and g1 on the same stream, no dependence between them.  Side by side in one launch

@@ -46,6 +46,20 @@ struct GemmArgs {
     int a_fmt = 0, b_fmt = 0;  // element format of each operand: 0 = E2M1 (q[R][C/2]), 1 = E4M3 (q[R][C])
 };
 
+// The kernels one GEMM is cut into: the tiled kernel on 256 x 256 or on 256 x 128 tiles for whole-tile blocks of the
+// output, the any-shape kernel for edge strips and everything else.  At most four parts.
+enum GemmKind { GEMM_ANY = 0, GEMM_TILED_256 = 1, GEMM_TILED_128 = 2 };
+struct GemmPart {
+    int kind;
+    int64_t r0, rows, c0, cols;  // block of the output: rows of A, rows of B
+};
+struct GemmPlan {
+    int n;
+    GemmPart part[4];
+};
+// host logic only (no device call); cus: compute units of the device the launch is planned for
+GemmPlan plan_gemm(const GemmArgs &g, int cus);
+
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);
 // two GEMMs that do not depend on each other (g0.accumulate must be 0); may share one launch
 hipError_t launch_gemm_pair(const GemmArgs &g0, const GemmArgs &g1, hipStream_t st);

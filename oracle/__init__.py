@@ -21,7 +21,7 @@ _SRC = os.path.join(_HERE, "mxfp4_oracle.c")
 _LIB = os.path.join(_HERE, "libmxfp4_oracle.so")
 
 AXIS_LAST, AXIS_FIRST = 0, 1
-HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16 = 0, 1, 2, 3
+HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16, HAD_RANDSIGN16 = 0, 1, 2, 3, 4
 RNE, SR = 0, 1
 FMT_E2M1, FMT_E4M3 = 0, 1
 

@@ -39,7 +39,7 @@
 #define MX_BLOCK 32
 
 enum { ORC_AXIS_LAST = 0, ORC_AXIS_FIRST = 1 };
-enum { ORC_HAD_NONE = 0, ORC_HAD_DET = 1, ORC_HAD_RANDSIGN = 2, ORC_HAD_DET16 = 3 };
+enum { ORC_HAD_NONE = 0, ORC_HAD_DET = 1, ORC_HAD_RANDSIGN = 2, ORC_HAD_DET16 = 3, ORC_HAD_RANDSIGN16 = 4 };
 enum { ORC_RNE = 0, ORC_SR = 1 };
 enum { ORC_FMT_E2M1 = 0, ORC_FMT_E4M3 = 1 };
 
@@ -248,7 +248,9 @@ void orc_wht(float *v, int n)
 /* Optional sign flips and rotation of one block v[0..31] (App. A.2), in place. */
 static void rotate_block(float *v, int had, uint32_t sign_mask)
 {
-    if (had == ORC_HAD_RANDSIGN)
+    /* randomised rotation: the block's +-1 diagonal first (entry i of the 32 for element i of the block,
+     * also when two 16-point rotations follow: Table 1 runs the randomised rotation at size 16) */
+    if (had == ORC_HAD_RANDSIGN || had == ORC_HAD_RANDSIGN16)
         for (int i = 0; i < MX_BLOCK; ++i)
             if ((sign_mask >> i) & 1u) v[i] = -v[i];
 
@@ -260,7 +262,7 @@ static void rotate_block(float *v, int had, uint32_t sign_mask)
             volatile float p = v[i] * c;
             v[i] = p;
         }
-    } else if (had == ORC_HAD_DET16) {
+    } else if (had == ORC_HAD_DET16 || had == ORC_HAD_RANDSIGN16) {
         /* two independent H16 / 4 per block */
         orc_wht(v, 16);
         orc_wht(v + 16, 16);

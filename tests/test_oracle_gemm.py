@@ -121,7 +121,8 @@ def test_linear_bwd_is_exact_on_grid_inputs():
     assert dx2.shape == (M, K) and dw2.shape == (N, K) and np.array_equal(dw2, dw)
 
 
-@pytest.mark.parametrize("had", [oracle.HAD_NONE, oracle.HAD_DET, oracle.HAD_RANDSIGN, oracle.HAD_DET16])
+@pytest.mark.parametrize("had", [oracle.HAD_NONE, oracle.HAD_DET, oracle.HAD_RANDSIGN, oracle.HAD_DET16,
+                                 oracle.HAD_RANDSIGN16])
 def test_quantised_linear_approximates_the_real_product(had):
     # the rotation must cancel inside the contraction (App. C): a missing normalisation, a
     # rotation along the wrong axis or a one-sided sign flip would leave an O(1) relative error

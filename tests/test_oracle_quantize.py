@@ -136,7 +136,8 @@ def test_block_independence(x_normal):
 
 
 # ------------------------------------------------------------ axes and strides
-@pytest.mark.parametrize("had", [oracle.HAD_NONE, oracle.HAD_DET, oracle.HAD_RANDSIGN, oracle.HAD_DET16])
+@pytest.mark.parametrize("had", [oracle.HAD_NONE, oracle.HAD_DET, oracle.HAD_RANDSIGN, oracle.HAD_DET16,
+                                 oracle.HAD_RANDSIGN16])
 def test_axis_first_is_axis_last_of_the_transpose(had):
     x = synth.as_u16(synth.normal(96, 80, 1.0, seed=4, stream=synth.STREAM_DY)).copy()
     qf, sf = oracle.quantize(x, axis=oracle.AXIS_FIRST, had=had, seed=9)
@@ -233,6 +234,31 @@ def test_random_sign_is_det_hadamard_of_the_sign_flipped_input():
     q4, s4 = oracle.quantize(xt, axis=oracle.AXIS_FIRST, had=oracle.HAD_RANDSIGN, seed=seed)
     q5, s5 = oracle.quantize(xt ^ flip_rows, axis=oracle.AXIS_FIRST, had=oracle.HAD_DET)
     assert np.array_equal(q4, q5) and np.array_equal(s4, s5)
+
+
+def test_random_sign_16_is_det16_of_the_sign_flipped_input():
+    # Table 1 runs the randomised rotation at size 16: the block's 32-entry diagonal, then two 16-point rotations.
+    # A diagonal of period 16, a missing flip or a 32-point rotation behind it would all fail here.
+    seed = 4242
+    x = synth.as_u16(synth.normal(32, 96, 1.0, seed=27, stream=synth.STREAM_X)).copy()
+    mask = oracle.sign_mask(seed)
+    assert (mask & 0xFFFF) != (mask >> 16)          # the two halves of the diagonal differ for this seed
+    flip = np.array([0x8000 if (mask >> (c % 32)) & 1 else 0 for c in range(96)], dtype=np.uint16)
+    q1, s1 = oracle.quantize(x, had=oracle.HAD_RANDSIGN16, seed=seed)
+    q2, s2 = oracle.quantize(x ^ flip[None, :], had=oracle.HAD_DET16)
+    assert np.array_equal(q1, q2) and np.array_equal(s1, s2)
+    q3, _ = oracle.quantize(x, had=oracle.HAD_RANDSIGN, seed=seed)
+    q4, _ = oracle.quantize(x, had=oracle.HAD_DET16)
+    assert not np.array_equal(q1, q3) and not np.array_equal(q1, q4)
+    xt = np.ascontiguousarray(x.T)                  # the diagonal runs along the contraction axis for AXIS_FIRST too
+    q5, s5 = oracle.quantize(xt, axis=oracle.AXIS_FIRST, had=oracle.HAD_RANDSIGN16, seed=seed)
+    q6, s6 = oracle.quantize(xt ^ flip[:, None], axis=oracle.AXIS_FIRST, had=oracle.HAD_DET16)
+    assert np.array_equal(q5, q6) and np.array_equal(s5, s6)
+    # 2D geometry and the MXFP8 quantiser take the same rotation
+    for fn in (oracle.quantize_2d, oracle.quantize_fp8):
+        a = fn(x, had=oracle.HAD_RANDSIGN16, seed=seed)
+        b = fn(x ^ flip[None, :], had=oracle.HAD_DET16)
+        assert all(np.array_equal(u, v) for u, v in zip(a, b))
 
 
 # ------------------------------------------------------------ stochastic rounding in tensors

@@ -8,7 +8,7 @@ import oracle
 from paper_2605_09825_amd import synth
 from test_oracle_quantize import bf16_bits, bits_to_f64, unpack
 
-HADS = [oracle.HAD_NONE, oracle.HAD_DET, oracle.HAD_RANDSIGN, oracle.HAD_DET16]
+HADS = [oracle.HAD_NONE, oracle.HAD_DET, oracle.HAD_RANDSIGN, oracle.HAD_DET16, oracle.HAD_RANDSIGN16]
 E2M1 = np.array([0, 0.5, 1, 1.5, 2, 3, 4, 6, -0.0, -0.5, -1, -1.5, -2, -3, -4, -6])
 
 

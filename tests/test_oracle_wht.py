@@ -94,3 +94,17 @@ def test_cancellation_with_random_signs_exact_on_integers():
     D = np.tile(d, 2)
     assert np.array_equal(rot_rows(X * D) @ rot_rows(W * D).T, 32 * (X @ W.T))
     assert 4 < (d < 0).sum() < 28  # the mask is not degenerate
+
+
+def test_cancellation_with_random_signs_and_16_point_rotations_exact_on_integers():
+    # (X D (H16 + H16))(W D (H16 + H16))^T = 16 X W^T: the randomised rotation of Table 1 (size 16) cancels too
+    rng = np.random.default_rng(4)
+    X = rng.integers(-8, 9, size=(32, 64))
+    W = rng.integers(-8, 9, size=(48, 64))
+    mask = oracle.sign_mask(78)
+    D = np.tile(np.array([-1 if (mask >> i) & 1 else 1 for i in range(32)]), 2)
+
+    def rot16(a):
+        return np.stack([np.concatenate([oracle.wht(r[i:i + 16].astype(np.float32)) for i in range(0, 64, 16)])
+                         for r in a]).astype(np.int64)
+    assert np.array_equal(rot16(X * D) @ rot16(W * D).T, 16 * (X @ W.T))

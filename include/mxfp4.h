@@ -59,7 +59,9 @@ typedef enum {
     MXFP4_HAD_NONE = 0,
     MXFP4_HAD_DET = 1,      /* deterministic H32/sqrt(32), Sylvester order                       */
     MXFP4_HAD_RANDSIGN = 2, /* H32/sqrt(32) after a seeded +-1 diagonal shared by all blocks     */
-    MXFP4_HAD_DET16 = 3     /* two independent H16/4 per block (the paper's H16 tiling)          */
+    MXFP4_HAD_DET16 = 3,    /* two independent H16/4 per block (the paper's H16 tiling)          */
+    MXFP4_HAD_RANDSIGN16 = 4 /* the same +-1 diagonal (32 entries per block), then two H16/4:
+                              * Table 1's randomised rotation runs at size 16               */
 } mxfp4_hadamard;
 
 /* FP4 cast of eq. (1). */
@@ -108,7 +110,7 @@ typedef struct {
  *            MXFP4_AXIS_FIRST: R = cols, C = rows, rows % 32 == 0, cols % 2 == 0;
  *                              x 4-byte aligned, ld % 2 == 0; q/s hold the quantised transpose
  *   q_out    uint8 [R][C/2], 16-byte aligned      s_out  uint8 [R][C/32]
- *   seed     used by MXFP4_HAD_RANDSIGN and MXFP4_SR only.  Its low 48 bits (the base seed)
+ *   seed     used by the two random-sign modes and MXFP4_SR only.  Its low 48 bits (the base seed)
  *            determine the random-sign diagonal; all 64 bits key the stochastic-rounding
  *            counters.  Both operands of a GEMM must use the same base seed and mode for the
  *            rotation to cancel in the product, and should differ in the high 16 bits

@@ -19,7 +19,7 @@ if os.environ.get("MXFP4_SANITIZE_HOST", "") not in ("", "0"):  # host-sanitizer
 # enums of include/mxfp4.h
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EDEVICE, ENOTIMPL = range(7)
 AXIS_LAST, AXIS_FIRST = 0, 1
-HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16 = 0, 1, 2, 3
+HAD_NONE, HAD_DET, HAD_RANDSIGN, HAD_DET16, HAD_RANDSIGN16 = 0, 1, 2, 3, 4
 RNE, SR = 0, 1
 OUT_BF16, OUT_FP32 = 0, 1
 GEOM_1D, GEOM_2D = 0, 1

@@ -35,7 +35,7 @@ int check_quantize(const void *x, int64_t rows, int64_t cols, int64_t ld, int ax
                    const void *q, const void *s)
 {
     if (axis != MXFP4_AXIS_LAST && axis != MXFP4_AXIS_FIRST) return MXFP4_EINVAL;
-    if (had < MXFP4_HAD_NONE || had > MXFP4_HAD_DET16) return MXFP4_EINVAL;
+    if (had < MXFP4_HAD_NONE || had > MXFP4_HAD_RANDSIGN16) return MXFP4_EINVAL;
     if (rnd != MXFP4_RNE && rnd != MXFP4_SR) return MXFP4_EINVAL;
     if (rows < 0 || cols < 0) return MXFP4_ESHAPE;
     if (rows == 0 || cols == 0) return MXFP4_OK;
@@ -135,7 +135,7 @@ SavedLayout saved_layout(int64_t M, int64_t N, int64_t K, const StageFormats &f)
 int check_cfg(const mxfp4_linear_cfg *cfg)
 {
     if (!cfg) return MXFP4_EINVAL;
-    if (cfg->hadamard < MXFP4_HAD_NONE || cfg->hadamard > MXFP4_HAD_DET16) return MXFP4_EINVAL;
+    if (cfg->hadamard < MXFP4_HAD_NONE || cfg->hadamard > MXFP4_HAD_RANDSIGN16) return MXFP4_EINVAL;
     if (cfg->rounding != MXFP4_RNE && cfg->rounding != MXFP4_SR) return MXFP4_EINVAL;
     const int32_t dts[3] = {cfg->y_dtype, cfg->dx_dtype, cfg->dw_dtype};
     for (int i = 0; i < 3; ++i)
@@ -208,7 +208,7 @@ static int prep_2d(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_el
                    void *s_first, QuantArgs &a)
 {
     const bool want_last = q_last || s_last, want_first = q_first || s_first;
-    if (hadamard < MXFP4_HAD_NONE || hadamard > MXFP4_HAD_DET16) return MXFP4_EINVAL;
+    if (hadamard < MXFP4_HAD_NONE || hadamard > MXFP4_HAD_RANDSIGN16) return MXFP4_EINVAL;
     if (rounding != MXFP4_RNE && rounding != MXFP4_SR) return MXFP4_EINVAL;
     if (rows < 0 || cols < 0) return MXFP4_ESHAPE;
     if (rows == 0 || cols == 0) return MXFP4_OK;

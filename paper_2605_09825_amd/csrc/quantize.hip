@@ -24,7 +24,7 @@
 namespace mxfp4 {
 namespace {
 
-constexpr int HAD_NONE = 0, HAD_DET = 1, HAD_RANDSIGN = 2, HAD_DET16 = 3;
+constexpr int HAD_NONE = 0, HAD_DET = 1, HAD_RANDSIGN = 2, HAD_DET16 = 3, HAD_RANDSIGN16 = 4;
 constexpr int64_t LLC_BYTES = int64_t(256) << 20;  // MI355X Infinity Cache
 constexpr int RND_RNE = 0, RND_SR = 1;
 
@@ -96,7 +96,7 @@ __device__ __forceinline__ uint32_t sr_code(float t, uint32_t r)
 template <int HAD>
 __device__ __forceinline__ void rotate_block(float (&v)[32], uint32_t sign_mask)
 {
-    if (HAD == HAD_RANDSIGN) {
+    if (HAD == HAD_RANDSIGN || HAD == HAD_RANDSIGN16) {  // the block's 32-entry diagonal, whatever the rotation size
 #pragma unroll
         for (int i = 0; i < 32; ++i)
             v[i] = __uint_as_float(__float_as_uint(v[i]) ^ (((sign_mask >> i) & 1u) << 31));
@@ -106,7 +106,7 @@ __device__ __forceinline__ void rotate_block(float (&v)[32], uint32_t sign_mask)
         const float c = __uint_as_float(0x3E3504F3u);  // 2^-2.5 rounded to fp32
 #pragma unroll
         for (int i = 0; i < 32; ++i) v[i] = v[i] * c;
-    } else if (HAD == HAD_DET16) {
+    } else if (HAD == HAD_DET16 || HAD == HAD_RANDSIGN16) {
         butterflies<16>(v);
 #pragma unroll
         for (int i = 0; i < 32; ++i) v[i] = v[i] * 0.25f;
@@ -693,6 +693,7 @@ hipError_t launch_cols_mode(const QuantArgs &a, const QuantArgs *b, hipStream_t 
         case HAD_NONE: return launch_cols_h<HAD_NONE, MODE>(a, b, st);
         case HAD_DET: return launch_cols_h<HAD_DET, MODE>(a, b, st);
         case HAD_RANDSIGN: return launch_cols_h<HAD_RANDSIGN, MODE>(a, b, st);
+        case HAD_RANDSIGN16: return launch_cols_h<HAD_RANDSIGN16, MODE>(a, b, st);
         default: return launch_cols_h<HAD_DET16, MODE>(a, b, st);
     }
 }
@@ -705,6 +706,7 @@ hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st)
         case HAD_NONE: return launch_rows_h<HAD_NONE>(a, st);
         case HAD_DET: return launch_rows_h<HAD_DET>(a, st);
         case HAD_RANDSIGN: return launch_rows_h<HAD_RANDSIGN>(a, st);
+        case HAD_RANDSIGN16: return launch_rows_h<HAD_RANDSIGN16>(a, st);
         default: return launch_rows_h<HAD_DET16>(a, st);
     }
 }
@@ -717,6 +719,7 @@ hipError_t launch_quantize_fp8(const QuantArgs &a, bool cols_axis, hipStream_t s
         case HAD_NONE: return launch_fp8_h<HAD_NONE>(a, cols_axis, st);
         case HAD_DET: return launch_fp8_h<HAD_DET>(a, cols_axis, st);
         case HAD_RANDSIGN: return launch_fp8_h<HAD_RANDSIGN>(a, cols_axis, st);
+        case HAD_RANDSIGN16: return launch_fp8_h<HAD_RANDSIGN16>(a, cols_axis, st);
         default: return launch_fp8_h<HAD_DET16>(a, cols_axis, st);
     }
 }

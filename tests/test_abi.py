@@ -48,6 +48,7 @@ def test_quantize_argument_errors(L):
     q = L.mxfp4_quantize
     assert q(P, 64, 64, 64, 2, 0, 0, 0, P, P, None) == mx.EINVAL          # axis
     assert q(P, 64, 64, 64, 0, 9, 0, 0, P, P, None) == mx.EINVAL          # hadamard
+    assert q(P, 64, 64, 64, 0, mx.HAD_RANDSIGN16 + 1, 0, 0, P, P, None) == mx.EINVAL
     assert q(P, 64, 64, 64, 0, 0, 2, 0, P, P, None) == mx.EINVAL          # rounding
     assert q(None, 64, 64, 64, 0, 0, 0, 0, P, P, None) == mx.EINVAL
     assert q(P, 64, 64, 64, 0, 0, 0, 0, None, P, None) == mx.EINVAL

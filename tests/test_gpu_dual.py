@@ -16,7 +16,7 @@ from test_gpu_linear import ws_slices
 
 pytestmark = pytest.mark.gpu
 
-HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16]
+HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16, mx.HAD_RANDSIGN16]
 RNDS = [mx.RNE, mx.SR]
 
 
@@ -115,7 +115,7 @@ def run_pair(x, w, dy, had, rnd, seed, full):
 
 
 @pytest.mark.parametrize("had,rnd", [(mx.HAD_NONE, mx.RNE), (mx.HAD_DET, mx.RNE), (mx.HAD_RANDSIGN, mx.RNE),
-                                     (mx.HAD_NONE, mx.SR), (mx.HAD_DET16, mx.RNE)])
+                                     (mx.HAD_NONE, mx.SR), (mx.HAD_DET16, mx.RNE), (mx.HAD_RANDSIGN16, mx.SR)])
 @pytest.mark.parametrize("shape", [(256, 512, 512), (96, 160, 224)])
 def test_training_pair(shape, had, rnd):
     M, N, K = shape

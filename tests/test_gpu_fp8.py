@@ -17,7 +17,7 @@ from test_gpu_gemm import assert_close, gpu
 pytestmark = pytest.mark.gpu
 FP8_RTOL = 7 * 2.0 ** -13 + 1e-5
 
-HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16]
+HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16, mx.HAD_RANDSIGN16]
 
 
 def check_q(t_cpu, axis, had, seed=0, x_gpu=None):

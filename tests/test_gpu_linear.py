@@ -28,7 +28,7 @@ def ws_slices(ws, M, N, K, bwd):
 
 
 @pytest.mark.parametrize("had,rnd", [(mx.HAD_NONE, mx.RNE), (mx.HAD_DET, mx.RNE), (mx.HAD_RANDSIGN, mx.RNE),
-                                     (mx.HAD_NONE, mx.SR), (mx.HAD_DET16, mx.RNE)])
+                                     (mx.HAD_NONE, mx.SR), (mx.HAD_DET16, mx.RNE), (mx.HAD_RANDSIGN16, mx.SR)])
 @pytest.mark.parametrize("shape", [(256, 512, 512), (96, 160, 224)])
 def test_linear_fwd_and_bwd(shape, had, rnd):
     M, N, K = shape

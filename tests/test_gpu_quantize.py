@@ -11,7 +11,7 @@ from gpu_util import first_mismatch, gpu_quantize
 
 pytestmark = pytest.mark.gpu
 
-HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16]
+HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16, mx.HAD_RANDSIGN16]
 RNDS = [mx.RNE, mx.SR]
 
 

@@ -15,7 +15,7 @@ from test_gpu_dual import saved_slices
 
 pytestmark = pytest.mark.gpu
 
-HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16]
+HADS = [mx.HAD_NONE, mx.HAD_DET, mx.HAD_RANDSIGN, mx.HAD_DET16, mx.HAD_RANDSIGN16]
 RNDS = [mx.RNE, mx.SR]
 
 

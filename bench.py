@@ -37,14 +37,14 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak
 BYTES_PER_ELEM = 2.0 + 0.5 + 1.0 / 32.0  # bf16 read + packed codes + scale byte per element
 BYTES_PER_ELEM_DUAL = 2.0 + 2 * (0.5 + 1.0 / 32.0)  # one read, both quantisations written
 
-# Bytes crossing the L2's outward port per GEMM launch (mean of the three GEMMs of a step): not measured in this
-# run but taken from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in the file named below (FETCH_SIZE
-# x 2.0 after calibration against a 256 MiB copy).  They include what the 256 MB Infinity Cache serves.
-GEMM_TRAFFIC_BYTES = 290.1e6
+# Bytes crossing the L2's outward port in one launch of the step's longest kernel (Dgrad and Wgrad side by side):
+# not measured in this run but taken from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in the file named
+# below (FETCH_SIZE x 2.0 after calibration against a 256 MiB copy): 419.50 MiB read + 160.02 MiB written.  They
+# include what the 256 MB Infinity Cache serves.
+GEMM_TRAFFIC_BYTES = 607.7e6
 GEMM_TRAFFIC_SOURCE = "profiles/qkv_traffic_counters.md"
-# operands once + output once, mean of Fprop (bf16 out), Dgrad (bf16 out), Wgrad (fp32 out)
-GEMM_ALGORITHMIC_BYTES = ((M * K + N * K) * 0.53125 + M * N * 2 + (M * N + K * N) * 0.53125 + M * K * 2 +
-                          (N * M + K * M) * 0.53125 + N * K * 4) / 3.0
+# operands once + outputs once: Dgrad (dY and W^T quantised, dX bf16) + Wgrad (dY^T and X^T quantised, dW fp32)
+GEMM_ALGORITHMIC_BYTES = (M * N + K * N) * 0.53125 + M * K * 2 + (N * M + K * M) * 0.53125 + N * K * 4
 REPEATS = 7  # repetitions of the timed region; the median is reported
 
 
@@ -432,9 +432,12 @@ def main() -> int:
         ("w_dual", lambda: q_dual(w, wq, wsc, sv_wtq, sv_wts)),
         ("fprop", lambda: mx.mxfp4_gemm(xq, xs, wq, wsc, out=y, out_dtype=mx.OUT_BF16)),
         ("dy_dual", lambda: q_dual(dy, gq, gs, gtq, gts)),
-        ("dgrad", lambda: mx.mxfp4_gemm(gq, gs, sv_wtq, sv_wts, out=dx, out_dtype=mx.OUT_BF16)),
-        ("wgrad", lambda: mx.mxfp4_gemm(gtq, gts, sv_xtq, sv_xts, out=dw, out_dtype=mx.OUT_FP32)),
+        ("dgrad+wgrad", lambda: mx.mxfp4_gemm_pair((gq, gs), (sv_wtq, sv_wts), dx, (gtq, gts), (sv_xtq, sv_xts), dw)),
     ]
+    single = {  # the two backward products as launches of their own (what the separate calls enqueue)
+        "dgrad": lambda: mx.mxfp4_gemm(gq, gs, sv_wtq, sv_wts, out=dx, out_dtype=mx.OUT_BF16),
+        "wgrad": lambda: mx.mxfp4_gemm(gtq, gts, sv_xtq, sv_xts, out=dw, out_dtype=mx.OUT_FP32),
+    }
     n_inst = min(args.steps, 100)
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in launches]
           for _ in range(n_inst)]
@@ -455,10 +458,12 @@ def main() -> int:
     # is what a kernel trace reports as well; both are printed.
     iters = min(max(5, args.steps), 50)
     t_fprop = event_time_ms(launches[2][1], iters, torch)
-    t_dgrad = event_time_ms(launches[4][1], iters, torch)
-    t_wgrad = event_time_ms(launches[5][1], iters, torch)
-    t_gemm = (t_fprop + t_dgrad + t_wgrad) / 3.0
-    gemm_tflops = 2.0 * M * N * K / (t_gemm * 1e-3) / 1e12
+    t_pair = event_time_ms(launches[4][1], iters, torch)
+    t_dgrad = event_time_ms(single["dgrad"], iters, torch)
+    t_wgrad = event_time_ms(single["wgrad"], iters, torch)
+    # the step's longest launch, Dgrad and Wgrad side by side (two GEMMs' flops), is the kernel of the roofline
+    pair_tflops = 2 * 2.0 * M * N * K / (t_pair * 1e-3) / 1e12
+    single_tflops = 2.0 * M * N * K / ((t_fprop + t_dgrad + t_wgrad) / 3.0 * 1e-3) / 1e12
     t_quant_total = t_k["x_dual"] + t_k["w_dual"] + t_k["dy_dual"]
 
     # the single-axis kernels on the same (cache-warm) operands, back to back
@@ -554,11 +559,11 @@ def main() -> int:
     fp8_rows_gbs, fp8_cols_gbs = gbs(M * K, t_fp8_rows, bpe8), gbs(M * K, t_fp8_cols, bpe8)
 
     # ---- shader clock during a sustained run of the dominant kernel ---------------------------------------
-    # (about a second of back-to-back launches of the step's three GEMMs on the step's operands)
+    # (about a second of back-to-back launches of the step's GEMM kernels on the step's operands: Fprop, then
+    # Dgrad and Wgrad side by side)
     def gemm_round():
         launches[2][1]()
         launches[4][1]()
-        launches[5][1]()
     for _ in range(20):
         gemm_round()
     torch.cuda.synchronize()
@@ -622,18 +627,23 @@ def main() -> int:
         "config": {
             "workload": "config 2: Llama-3.1-8B fused QKV linear, Fprop+Dgrad+Wgrad, M=8192 K=4096 N=6144, "
                         "deterministic H32 + MXFP4 RNE on both operands of each GEMM; y,dx bf16, dw fp32",
-            "M": M, "K": K, "N": N, "launches_per_step": 5,
+            "M": M, "K": K, "N": N, "launches_per_step": 4,
             "calls": "mxfp4_linear_fwd_save + mxfp4_linear_bwd_saved",
         },
         "separate_calls_ms_per_step": round(ms_separate, 4),
         "pct_of_fp4_peak_incl_quant": round(100.0 * tflops_incl / PEAK_FP4_TFLOPS, 2),
         "roofline": {
-            "kernel": "mxfp4 gemm (mean of fprop, dgrad, wgrad launches)",
+            "kernel": "gemm_tile_pair_kernel: Dgrad 8192x4096x6144 (bf16 out) and Wgrad 6144x4096x8192 (fp32 out) side "
+                      "by side in one launch, the longest kernel of the step",
             "bound": "mfma",
-            "achieved": round(gemm_tflops, 2),
+            "achieved": round(pair_tflops, 2),
             "peak": PEAK_FP4_TFLOPS,
             "unit": "TFLOP/s",
-            "frac": round(gemm_tflops / PEAK_FP4_TFLOPS, 4),
+            "frac": round(pair_tflops / PEAK_FP4_TFLOPS, 4),
+            "flop_per_launch": 2 * 2.0 * M * N * K,
+            "single_launches": {"what": "Fprop, Dgrad and Wgrad as launches of their own, mean",
+                                "achieved": round(single_tflops, 2),
+                                "frac": round(single_tflops / PEAK_FP4_TFLOPS, 4)},
             "traffic": GEMM_TRAFFIC_BYTES,
             "traffic_source": GEMM_TRAFFIC_SOURCE + " (rocprofv3 FETCH_SIZE + WRITE_SIZE at the L2's outward port, "
                               "Infinity Cache hits included; not measured in this run)",
@@ -644,8 +654,9 @@ def main() -> int:
             "sustained_tflops": round(gemm_tflops_sustained, 2),
             "peak_at_measured_clock": round(peak_at_clock, 1) if peak_at_clock else None,
             "frac_at_measured_clock": round(gemm_tflops_sustained / peak_at_clock, 4) if peak_at_clock else None,
-            "launch_ms": {"fprop": round(t_fprop, 4), "dgrad": round(t_dgrad, 4), "wgrad": round(t_wgrad, 4)},
-            "in_step_bracket_ms": {k: round(t_k[k], 4) for k in ("fprop", "dgrad", "wgrad")},
+            "launch_ms": {"dgrad+wgrad": round(t_pair, 4), "fprop": round(t_fprop, 4), "dgrad": round(t_dgrad, 4),
+                          "wgrad": round(t_wgrad, 4)},
+            "in_step_bracket_ms": {k: round(t_k[k], 4) for k in ("fprop", "dgrad+wgrad")},
         },
         "quantizer": {
             "bound": "hbm",
@@ -668,7 +679,7 @@ def main() -> int:
             "in_step_ms": {k: round(v, 4) for k, v in t_q.items()},
             "in_step_gbs_cache_warm": {k: round(gbs(elems[k], t_q[k]), 1) for k in elems},
         },
-        "breakdown_ms": {"gemm_total": round(t_k["fprop"] + t_k["dgrad"] + t_k["wgrad"], 4),
+        "breakdown_ms": {"gemm_total": round(t_k["fprop"] + t_k["dgrad+wgrad"], 4),
                          "quantize_total": round(t_quant_total, 4),
                          "note": "event brackets inside a second timed region; each includes the dispatch gap"},
     }
@@ -676,7 +687,7 @@ def main() -> int:
     if not args.no_other_configs:
         # totals of the other benchmark configurations, same conventions (free the headline's buffers first)
         del x, w, dy, y, dx, dw, ws_f, ws_b, saved, xq, xs, wq, wsc, gq, gs, wtq, wts, gtq, gts, xtq, xts
-        del sv_wtq, sv_wts, sv_xtq, sv_xts, launches
+        del sv_wtq, sv_wts, sv_xtq, sv_xts, launches, single
         torch.cuda.empty_cache()
         out["configs"] = []
         for c in (1, 3, 4, 5):

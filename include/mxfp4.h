@@ -198,6 +198,22 @@ int mxfp4_gemm(const void *a_q, const void *a_s, const void *b_q, const void *b_
                int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate, void *hip_stream);
 
 /*
+ * Two independent MXFP4 GEMMs enqueued together: the Dgrad and the Wgrad product of one layer share no
+ * operand buffer and no output (App. C.2, C.3; Fig. 3), so they can run side by side.  Each problem is
+ * described as in mxfp4_gemm (E2M1 operands); problem 0 never accumulates, problem 1 may (fp32 output).
+ * When both shapes fit the tiled kernel and together fill the chip, one launch runs them on disjoint sets
+ * of compute units split in proportion to their work; otherwise the call is mxfp4_gemm on problem 0
+ * followed by mxfp4_gemm on problem 1.  Results are bit for bit those of the two separate calls.
+ * The two outputs must not overlap each other or any operand.  Arguments are checked for both problems
+ * before anything is enqueued.
+ */
+int mxfp4_gemm_pair(const void *a0_q, const void *a0_s, const void *b0_q, const void *b0_s, int64_t R_a0,
+                    int64_t R_b0, int64_t C0, void *out0, int64_t ld_out0, int out_dtype0,
+                    const void *a1_q, const void *a1_s, const void *b1_q, const void *b1_s, int64_t R_a1,
+                    int64_t R_b1, int64_t C1, void *out1, int64_t ld_out1, int out_dtype1, int accumulate1,
+                    void *hip_stream);
+
+/*
  * Which kernels mxfp4_gemm_fmt cuts a product of this shape into on a device with `compute_units` compute
  * units (256 on MI355X), for operands and an output aligned as those calls demand: the tiled kernel of the
  * block-scaled FP4 GEMM (Sec. 2.1) on 256 x 256 tiles or, where those would leave compute units idle, on

@@ -26,7 +26,7 @@ GEOM_1D, GEOM_2D = 0, 1
 FMT_E2M1, FMT_E4M3 = 0, 1
 
 EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_quantize_fp8", "mxfp4_gemm",
-           "mxfp4_gemm_fmt", "mxfp4_gemm_plan", "mxfp4_linear_fwd", "mxfp4_linear_fwd_static", "mxfp4_linear_bwd",
+           "mxfp4_gemm_fmt", "mxfp4_gemm_pair", "mxfp4_gemm_plan", "mxfp4_linear_fwd", "mxfp4_linear_fwd_static", "mxfp4_linear_bwd",
            "mxfp4_linear_fwd_save", "mxfp4_linear_bwd_saved", "mxfp4_linear_saved_bytes",
            "mxfp4_linear_saved_layout", "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout",
            "mxfp4_status_string")
@@ -80,6 +80,9 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
         L.mxfp4_linear_fwd.restype = ci
         L.mxfp4_linear_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ctypes.POINTER(LinearCfg), vp, sz, vp]
+        L.mxfp4_gemm_pair.restype = ci
+        L.mxfp4_gemm_pair.argtypes = ([vp, vp, vp, vp, i64, i64, i64, vp, i64, ci] +
+                                      [vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci] + [vp])
         L.mxfp4_gemm_plan.restype = ci
         L.mxfp4_gemm_plan.argtypes = [i64, i64, i64, ci, ci, i64, ci, ctypes.POINTER(ci), ctypes.POINTER(i64)]
         L.mxfp4_linear_fwd_static.restype = ci
@@ -211,6 +214,22 @@ def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumula
                                                       Ra, Rb, C, _ptr(out), ld, out_dtype, int(accumulate),
                                                       _stream_ptr(stream)))
     return out
+
+
+def mxfp4_gemm_pair(a0, b0, out0, a1, b1, out1, accumulate1: bool = False, stream=None):
+    """Two independent MXFP4 GEMMs enqueued together (Dgrad and Wgrad of one layer): a0, b0, a1, b1 are
+    (codes, scales) pairs of uint8 CUDA tensors, out0 / out1 preallocated bf16 or fp32 matrices."""
+    import torch
+    args = []
+    for (aq, as_), (bq, bs), out in ((a0, b0, out0), (a1, b1, out1)):
+        Ra, Rb, C = aq.shape[0], bq.shape[0], aq.shape[1] * 2
+        assert bq.shape[1] * 2 == C and all(t.is_contiguous() for t in (aq, as_, bq, bs))
+        assert tuple(out.shape) == (Ra, Rb) and (out.numel() == 0 or out.stride(1) == 1)
+        ld = out.stride(0) if Ra > 1 else max(Rb, out.stride(0))
+        args += [_ptr(aq), _ptr(as_), _ptr(bq), _ptr(bs), Ra, Rb, C, _ptr(out), ld,
+                 OUT_FP32 if out.dtype == torch.float32 else OUT_BF16]
+    _check("mxfp4_gemm_pair", lib().mxfp4_gemm_pair(*args, int(accumulate1), _stream_ptr(stream)))
+    return out0, out1
 
 
 GEMM_ANY, GEMM_TILED_256, GEMM_TILED_128 = 0, 1, 2

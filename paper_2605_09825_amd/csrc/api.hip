@@ -292,6 +292,33 @@ int mxfp4_gemm_fmt(const void *a_q, const void *a_s, int a_format, const void *b
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
+int mxfp4_gemm_pair(const void *a0_q, const void *a0_s, const void *b0_q, const void *b0_s, int64_t R_a0,
+                    int64_t R_b0, int64_t C0, void *out0, int64_t ld_out0, int out_dtype0,
+                    const void *a1_q, const void *a1_s, const void *b1_q, const void *b1_s, int64_t R_a1,
+                    int64_t R_b1, int64_t C1, void *out1, int64_t ld_out1, int out_dtype1, int accumulate1,
+                    void *hip_stream)
+{
+    const int rc0 = check_gemm(a0_q, a0_s, b0_q, b0_s, R_a0, R_b0, C0, out0, ld_out0, out_dtype0, 0);
+    if (rc0 > 0) return rc0;
+    const int rc1 = check_gemm(a1_q, a1_s, b1_q, b1_s, R_a1, R_b1, C1, out1, ld_out1, out_dtype1, accumulate1);
+    if (rc1 > 0) return rc1;
+    if (rc0 == 0 && rc1 == 0) return MXFP4_OK;  // both empty
+    if (!device_ok()) return MXFP4_EDEVICE;
+    const GemmArgs g0{static_cast<const uint8_t *>(a0_q), static_cast<const uint8_t *>(a0_s),
+                      static_cast<const uint8_t *>(b0_q), static_cast<const uint8_t *>(b0_s),
+                      R_a0, R_b0, C0, out0, ld_out0, out_dtype0 == MXFP4_OUT_FP32, 0, MXFP4_FMT_E2M1, MXFP4_FMT_E2M1};
+    const GemmArgs g1{static_cast<const uint8_t *>(a1_q), static_cast<const uint8_t *>(a1_s),
+                      static_cast<const uint8_t *>(b1_q), static_cast<const uint8_t *>(b1_s),
+                      R_a1, R_b1, C1, out1, ld_out1, out_dtype1 == MXFP4_OUT_FP32, accumulate1, MXFP4_FMT_E2M1,
+                      MXFP4_FMT_E2M1};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (rc0 == 0) e = launch_gemm(g1, st);        // one of the two is empty: the other alone
+    else if (rc1 == 0) e = launch_gemm(g0, st);
+    else e = launch_gemm_pair(g0, g1, st);
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
 int mxfp4_gemm_plan(int64_t R_a, int64_t R_b, int64_t C, int a_format, int b_format, int64_t ld_out,
                     int compute_units, int *n_parts, int64_t parts[20])
 {

@@ -80,6 +80,22 @@ def test_gemm_argument_errors(L):
     assert g(P, P, P, P, 0, 16, 32, None, 16, 1, 0, None) == mx.OK        # empty
 
 
+def test_gemm_pair_argument_errors(L):
+    g = L.mxfp4_gemm_pair
+    ok0 = (P, P, P, P, 16, 16, 32, P, 16, mx.OUT_BF16)
+    ok1 = (P, P, P, P, 16, 16, 32, P, 16, mx.OUT_FP32, 0)
+    assert g(*ok0[:9], 5, *ok1, None) == mx.EINVAL                         # dtype of problem 0
+    assert g(*ok0, *ok1[:9], mx.OUT_BF16, 1, None) == mx.EINVAL            # problem 1 accumulating into bf16
+    assert g(*ok0[:6], 48, *ok0[7:], *ok1, None) == mx.ESHAPE              # C0 % 32
+    assert g(*ok0, P, P, P, P, 16, 16, 32, P, 8, mx.OUT_FP32, 0, None) == mx.ESHAPE   # ld1 < R_b1
+    assert g(*ok0, None, P, P, P, 16, 16, 32, P, 16, mx.OUT_FP32, 0, None) == mx.EINVAL
+    assert g(P + 4, *ok0[1:], *ok1, None) == mx.EALIGN
+    empty0 = (None, None, None, None, 0, 16, 32, None, 16, mx.OUT_BF16)
+    empty1 = (None, None, None, None, 16, 0, 32, None, 16, mx.OUT_FP32, 0)
+    assert g(*empty0, *empty1, None) == mx.OK                              # both empty: nothing to enqueue
+    assert g(*empty0, *ok1[:9], mx.OUT_BF16, 1, None) == mx.EINVAL         # the other problem is still checked
+
+
 def test_linear_argument_errors_and_workspace(L):
     cfg = mx.make_cfg()
     M, N, K = 64, 96, 128

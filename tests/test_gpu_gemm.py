@@ -309,3 +309,29 @@ def test_config2_shape_every_tile():
     torch.cuda.synchronize()
     structured_check(y.cpu().numpy(), (xq.cpu().numpy(), xs.cpu().numpy()), (wq.cpu().numpy(), ws.cpu().numpy()),
                      np.random.default_rng(0))
+
+
+@pytest.mark.parametrize("shapes,acc", [
+    (((4096, 2048, 4096), (4096, 2048, 4096)), False),   # 128 + 128 tiles, equal work: side by side, 128 CUs each
+    (((4096, 4096, 1024), (2048, 4096, 1024)), True),    # 256 + 128 tiles: split 21 : 11 per XCD, second accumulating
+    (((512, 256, 1024), (96, 160, 224)), False),         # too few tiles / ragged: one after the other
+    (((300, 520, 1024), (0, 64, 64)), False),            # the second product empty
+])
+def test_gemm_pair_equals_the_two_separate_calls(shapes, acc):
+    # two independent products (App. C.2, C.3) in one call: bit for bit the results of two mxfp4_gemm calls, and
+    # the first of them against the oracle
+    rng = np.random.default_rng(sum(shapes[0]) + sum(shapes[1]))
+    ops = []
+    for Ra, Rb, C in shapes:
+        ops.append(tuple(gpu(t) for t in rand_operand(rng, Ra, C) + rand_operand(rng, Rb, C)))
+    (a0q, a0s, b0q, b0s), (a1q, a1s, b1q, b1s) = ops
+    base = torch.full((shapes[1][0], shapes[1][1]), 0.5, dtype=torch.float32, device="cuda:0")
+    want0 = mx.mxfp4_gemm(a0q, a0s, b0q, b0s, out_dtype=mx.OUT_BF16)
+    want1 = mx.mxfp4_gemm(a1q, a1s, b1q, b1s, out=base.clone(), out_dtype=mx.OUT_FP32, accumulate=acc)
+    out0 = torch.empty_like(want0)
+    out1 = base.clone()
+    mx.mxfp4_gemm_pair((a0q, a0s), (b0q, b0s), out0, (a1q, a1s), (b1q, b1s), out1, accumulate1=acc)
+    torch.cuda.synchronize()
+    assert torch.equal(out0, want0) and torch.equal(out1, want1)
+    ref, absum = oracle.gemm(*(t.cpu().numpy() for t in ops[0]))
+    close_bf16(out0.float().cpu().numpy(), ref, absum)

@@ -39,9 +39,9 @@ BYTES_PER_ELEM_DUAL = 2.0 + 2 * (0.5 + 1.0 / 32.0)  # one read, both quantisatio
 
 # Bytes crossing the L2's outward port in one launch of the step's longest kernel (Dgrad and Wgrad side by side):
 # not measured in this run but taken from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in the file named
-# below (FETCH_SIZE x 2.0 after calibration against a 256 MiB copy): 419.50 MiB read + 160.02 MiB written.  They
+# below (FETCH_SIZE x 2.0 after calibration against a 256 MiB copy): 421.23 MiB read + 160.01 MiB written.  They
 # include what the 256 MB Infinity Cache serves.
-GEMM_TRAFFIC_BYTES = 607.7e6
+GEMM_TRAFFIC_BYTES = 609.5e6
 GEMM_TRAFFIC_SOURCE = "profiles/qkv_traffic_counters.md"
 # operands once + outputs once: Dgrad (dY and W^T quantised, dX bf16) + Wgrad (dY^T and X^T quantised, dW fp32)
 GEMM_ALGORITHMIC_BYTES = (M * N + K * N) * 0.53125 + M * K * 2 + (N * M + K * M) * 0.53125 + N * K * 4

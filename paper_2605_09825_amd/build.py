@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmxfp4.so")
-SOURCES = ["api.hip", "quantize.hip", "gemm.hip"]
+SOURCES = ["api.hip", "quantize.hip", "quantize_fp8.hip", "gemm.hip"]
 
 # -ffp-contract=off: the quantiser's fp32 butterflies must round after every operation.
 # The -target-feature pair switches packed-fp32 code generation off (device pass only; the
@@ -37,16 +37,30 @@ if SANITIZE_HOST:
                                                 "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source into paper_2605_09825_amd/libmxfp4.so (always recompiles)."""
-    cmd = [hipcc()] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+def _run(cmd) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+    return err
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every HIP source into paper_2605_09825_amd/libmxfp4.so (always recompiles): the sources side by
+    side into objects in a scratch folder, then one link."""
+    import concurrent.futures
+    import tempfile
+    cc = hipcc()
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="mxfp4_build_") as tmp:
+        objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
+        cmds = [[cc] + compile_flags + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+        with concurrent.futures.ThreadPoolExecutor(max_workers=len(cmds)) as pool:
+            errs = list(pool.map(_run, cmds))
+        errs.append(_run([cc] + FLAGS + objs + ["-o", LIB]))
+    if verbose and any(e.strip() for e in errs):
+        print("\n".join(e for e in errs if e.strip()))
     return LIB
 
 

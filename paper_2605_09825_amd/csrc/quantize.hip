@@ -20,111 +20,12 @@
 //   * 32 x 32 geometry (App. D): the same kernel with the block maxima reduced over the
 //     16 lanes that share a region before the codes are formed.
 #include "mxfp4_internal.h"
+#include "quantize_block.h"
 
 namespace mxfp4 {
 namespace {
 
-constexpr int HAD_NONE = 0, HAD_DET = 1, HAD_RANDSIGN = 2, HAD_DET16 = 3, HAD_RANDSIGN16 = 4;
 constexpr int64_t LLC_BYTES = int64_t(256) << 20;  // MI355X Infinity Cache
-constexpr int RND_RNE = 0, RND_SR = 1;
-
-// ---- counter hash: stateless 32-bit mixer applied to (seed, index) -----------------
-struct RngKey {
-    uint32_t seed_lo_mul;  // low seed word times the odd constant
-    uint32_t seed_hi_mix;  // mixed high seed word
-};
-
-__host__ __device__ __forceinline__ uint32_t mix32(uint32_t x)
-{
-    x ^= x >> 16;
-    x *= 0x9E3779B9u;
-    x ^= x >> 15;
-    x *= 0xBB67AE85u;
-    x ^= x >> 16;
-    return x;
-}
-
-__host__ __device__ __forceinline__ uint32_t rand32(RngKey k, uint64_t idx)
-{
-    return mix32(mix32((uint32_t)idx + k.seed_lo_mul) ^ (uint32_t)(idx >> 32) ^ k.seed_hi_mix);
-}
-
-RngKey make_key(uint64_t seed)
-{
-    RngKey k;
-    k.seed_lo_mul = (uint32_t)seed * 0x9E3779B9u;
-    k.seed_hi_mix = mix32((uint32_t)(seed >> 32) ^ 0x6A09E667u);
-    return k;
-}
-
-// the +-1 diagonal of the random-sign rotation: a function of the base seed alone
-uint32_t sign_mask_of(uint64_t seed) { return rand32(make_key(seed & SEED_BASE_MASK), 0xFFFFFFFFFFFFFFFFull); }
-
-// ---- one block in registers ---------------------------------------------------------
-template <int N>
-__device__ __forceinline__ void butterflies(float (&v)[32])
-{
-#pragma unroll
-    for (int h = 1; h < N; h <<= 1) {
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            if ((i & h) == 0) {
-                float a = v[i], b = v[i + h];
-                v[i] = a + b;
-                v[i + h] = a - b;
-            }
-        }
-    }
-}
-
-// Stochastic rounding of |t| (already divided by the block scale) to an E2M1 magnitude code.
-__device__ __forceinline__ uint32_t sr_code(float t, uint32_t r)
-{
-    float a = fminf(fabsf(t), 6.0f);
-    bool lo = a < 2.0f, mid = a < 4.0f;
-    float inv_delta = lo ? 2.0f : (mid ? 1.0f : 0.5f);
-    float q = a * inv_delta;  // exact: power-of-two factor
-    float fl = floorf(q);
-    float f = q - fl;  // exact
-    float u = (float)(2u * (r >> 9) + 1u) * 0x1p-24f;  // odd multiple of 2^-24 below 1: exact
-    uint32_t m = (uint32_t)fl + ((u < f) ? 1u : 0u);
-    uint32_t code = m + (lo ? 0u : (mid ? 2u : 4u));
-    return code | ((__float_as_uint(t) >> 28) & 8u);
-}
-
-// Optional sign flips and rotation of one block, in place (App. A.2).
-template <int HAD>
-__device__ __forceinline__ void rotate_block(float (&v)[32], uint32_t sign_mask)
-{
-    if (HAD == HAD_RANDSIGN || HAD == HAD_RANDSIGN16) {  // the block's 32-entry diagonal, whatever the rotation size
-#pragma unroll
-        for (int i = 0; i < 32; ++i)
-            v[i] = __uint_as_float(__float_as_uint(v[i]) ^ (((sign_mask >> i) & 1u) << 31));
-    }
-    if (HAD == HAD_DET || HAD == HAD_RANDSIGN) {
-        butterflies<32>(v);
-        const float c = __uint_as_float(0x3E3504F3u);  // 2^-2.5 rounded to fp32
-#pragma unroll
-        for (int i = 0; i < 32; ++i) v[i] = v[i] * c;
-    } else if (HAD == HAD_DET16 || HAD == HAD_RANDSIGN16) {
-        butterflies<16>(v);
-#pragma unroll
-        for (int i = 0; i < 32; ++i) v[i] = v[i] * 0.25f;
-    }
-}
-
-// Bit pattern of the block's largest magnitude.  V_MAXIMUM3_F32 (two new values per instruction, |.| as source
-// modifiers) returns NaN if any input is NaN, so a NaN or an infinity anywhere in the block shows as an exponent
-// field of 255, as in a comparison of the bit patterns.
-__device__ __forceinline__ uint32_t amax_bits(const float (&v)[32])
-{
-    float m = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 32; i += 2)
-        m = __builtin_elementwise_maximum(
-            __builtin_elementwise_maximum(__builtin_fabsf(v[i]), __builtin_fabsf(v[i + 1])), m);
-    return __float_as_uint(m) & 0x7FFFFFFFu;
-}
 
 // FP4 codes of one rotated block under the scale that follows from the shared maximum `amax` (bit
 // pattern): eq. (1) with the OCP scale rule.  idx0: linear index of element 0 in the quantised output
@@ -191,25 +92,6 @@ __device__ __forceinline__ void store_codes(uint4 *p, uint4 v, int streaming)
     }
 }
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-
-// 32 contiguous bf16 (four 16-byte words) widened to fp32
-__device__ __forceinline__ void widen(const uint4 (&raw)[4], float (&v)[32])
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        v[8 * j + 0] = bf16_lo(raw[j].x);
-        v[8 * j + 1] = bf16_hi(raw[j].x);
-        v[8 * j + 2] = bf16_lo(raw[j].y);
-        v[8 * j + 3] = bf16_hi(raw[j].y);
-        v[8 * j + 4] = bf16_lo(raw[j].z);
-        v[8 * j + 5] = bf16_hi(raw[j].z);
-        v[8 * j + 6] = bf16_lo(raw[j].w);
-        v[8 * j + 7] = bf16_hi(raw[j].w);
-    }
-}
-
 // ---- row-wise (1x32) ---------------------------------------------------------------------
 // One lane per block.  nblocks = rows * (cols/32); block g is row g / bpr, column block g % bpr.
 // STREAM: tensor larger than the last-level cache: non-temporal code stores.
@@ -245,7 +127,6 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
 
 // ---- column-wise (32x1) ------------------------------------------------------------------
 // Workgroup tile: 256 rows (8 row blocks, one per wave) x 128 columns (2 per lane).
-constexpr int CT_COLS = 128, CT_RB = 8;
 
 // MODE_DUAL: additionally emit the row-wise quantisation q_row[rows][cols/2], s_row[rows][cols/32] of the
 // same tile (needs cols % 32 == 0).  Each wave parks its 32 x 128 elements in LDS and reads them back as
@@ -256,17 +137,7 @@ constexpr int CT_COLS = 128, CT_RB = 8;
 // q/s or q_row/s_row).  Each phase runs twice over its data: first the maxima, reduced across the 16 lanes
 // that share a region, then the codes.
 constexpr int MODE_COLS = 0, MODE_DUAL = 1, MODE_2D = 2;
-constexpr int RAW_PITCH = 272;  // bytes per parked row: 256 + 16, so that the 16-byte reads below (16 lanes =
-                                // 4 rows x 4 blocks per issue) and the dword writes touch every bank once
 constexpr int LDS_S_BYTES = CT_COLS * CT_RB;
-
-// Orders the LDS accesses of one wave (which the hardware performs in program order) for the compiler too.
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 __device__ __forceinline__ uint32_t max_across(uint32_t m, int xor_mask)
 {
@@ -491,138 +362,6 @@ __global__ __launch_bounds__(512) void quantize_cols_kernel(const TileJob job0, 
     }
 }
 
-// ---- MXFP8 (E4M3 elements) for the stages that stay in 8 bits (Table 1, "others FP8") --------------
-// Same rotation, same block maximum; scale byte = biased exponent of the maximum - 8 (E4M3's largest
-// exponent), one byte per element.  V_CVT_SCALEF32_PK_FP8_F32 divides by the scale and rounds to nearest
-// even (probed, subnormals included) but turns everything above 464 into NaN instead of saturating, so
-// the values are clamped to +-448 * 2^E first.
-typedef short v2s __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ void encode_scaled_fp8(const float (&v)[32], uint32_t amax, uint4 &lo, uint4 &hi,
-                                                  uint32_t &scale_byte)
-{
-    const uint32_t eb = amax >> 23;
-    const bool bad = (eb == 255u);
-    const uint32_t sb = eb > 8u ? eb - 8u : 0u;  // eb <= 254 here, so sb <= 246
-    scale_byte = bad ? 0xFFu : sb;
-    const float scale = __uint_as_float(sb << 23);
-    const float lim = __uint_as_float(((sb + 8u) << 23) | 0x600000u);  // 448 * 2^(sb - 127)
-    uint32_t w[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        v2s r = {0, 0};
-        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, __builtin_amdgcn_fmed3f(v[4 * j + 0], -lim, lim),
-                                                     __builtin_amdgcn_fmed3f(v[4 * j + 1], -lim, lim), scale, false);
-        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, __builtin_amdgcn_fmed3f(v[4 * j + 2], -lim, lim),
-                                                     __builtin_amdgcn_fmed3f(v[4 * j + 3], -lim, lim), scale, true);
-        w[j] = (uint32_t)(uint16_t)r.x | ((uint32_t)(uint16_t)r.y << 16);
-    }
-    lo = bad ? make_uint4(0, 0, 0, 0) : make_uint4(w[0], w[1], w[2], w[3]);
-    hi = bad ? make_uint4(0, 0, 0, 0) : make_uint4(w[4], w[5], w[6], w[7]);
-}
-
-// row-wise: one lane per block, 32 output bytes per lane
-template <int HAD>
-__global__ __launch_bounds__(256) void quantize_rows_fp8_kernel(const uint16_t *__restrict__ x, int64_t nblocks,
-                                                                int64_t bpr, int64_t ld, int dense,
-                                                                uint32_t sign_mask, uint8_t *__restrict__ q,
-                                                                uint8_t *__restrict__ s)
-{
-    int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (g >= nblocks) return;
-    const uint16_t *src;
-    if (dense) {
-        src = x + g * 32;
-    } else {
-        int64_t row = g / bpr;
-        src = x + row * ld + (g - row * bpr) * 32;
-    }
-    const uint4 *p = reinterpret_cast<const uint4 *>(src);
-    uint4 raw[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) raw[j] = p[j];
-    float v[32];
-    widen(raw, v);
-    rotate_block<HAD>(v, sign_mask);
-    uint4 lo, hi;
-    uint32_t sb;
-    encode_scaled_fp8(v, amax_bits(v), lo, hi, sb);
-    reinterpret_cast<uint4 *>(q)[2 * g] = lo;
-    reinterpret_cast<uint4 *>(q)[2 * g + 1] = hi;
-    s[g] = (uint8_t)sb;
-}
-
-// column-wise: the tile and lane assignment of quantize_cols_kernel; an output row receives 8 x 32 = 256
-// contiguous bytes per tile
-template <int HAD>
-__global__ __launch_bounds__(512) void quantize_cols_fp8_kernel(const uint16_t *__restrict__ x, int64_t rows,
-                                                                int64_t cols, int64_t ld, uint32_t sign_mask,
-                                                                uint8_t *__restrict__ q, uint8_t *__restrict__ s,
-                                                                uint32_t col_groups)
-{
-    __shared__ uint4 lds_q[CT_RB][2][CT_COLS + 1];
-    __shared__ uint8_t lds_s[CT_COLS][CT_RB];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const uint32_t by = blockIdx.x / col_groups, bx = blockIdx.x - by * col_groups;
-    const int64_t c0 = (int64_t)bx * CT_COLS, rb0 = (int64_t)by * CT_RB, nrb = rows >> 5;
-    const int64_t rb = rb0 + w, col = c0 + 2 * lane;
-    uint32_t raw[32];
-    if ((rb < nrb) && (col < cols)) {
-        const uint16_t *p = x + (rb * 32) * ld + col;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint32_t *>(p + i * ld);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 32; ++i) raw[i] = 0;
-    }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        float v[32];
-#pragma unroll
-        for (int i = 0; i < 32; ++i) v[i] = j == 0 ? bf16_lo(raw[i]) : bf16_hi(raw[i]);
-        rotate_block<HAD>(v, sign_mask);
-        uint4 lo, hi;
-        uint32_t sb;
-        encode_scaled_fp8(v, amax_bits(v), lo, hi, sb);
-        lds_q[w][0][2 * lane + j] = lo;
-        lds_q[w][1][2 * lane + j] = hi;
-        lds_s[2 * lane + j][w] = (uint8_t)sb;
-    }
-    __syncthreads();
-    // 16 consecutive threads write the 256 bytes one output row receives from this tile
-#pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-        const int idx = pass * 512 + tid, cl = idx >> 4, k = idx & 15, b = k >> 1, half = k & 1;
-        if (c0 + cl < cols && rb0 + b < nrb)
-            *reinterpret_cast<uint4 *>(q + (c0 + cl) * rows + (rb0 + b) * 32 + half * 16) = lds_q[b][half][cl];
-    }
-    if (tid < CT_COLS && c0 + tid < cols) {
-        uint8_t *dst = s + (c0 + tid) * nrb + rb0;
-#pragma unroll
-        for (int k = 0; k < CT_RB; ++k)
-            if (rb0 + k < nrb) dst[k] = lds_s[tid][k];
-    }
-}
-
-template <int HAD>
-hipError_t launch_fp8_h(const QuantArgs &a, bool cols_axis, hipStream_t st)
-{
-    const uint32_t sign_mask = sign_mask_of(a.seed);
-    if (cols_axis) {
-        const int64_t nrb = a.rows / 32;
-        const uint32_t col_groups = (uint32_t)((a.cols + CT_COLS - 1) / CT_COLS);
-        dim3 grid((unsigned)(col_groups * ((nrb + CT_RB - 1) / CT_RB)));
-        hipLaunchKernelGGL((quantize_cols_fp8_kernel<HAD>), grid, dim3(512), 0, st, a.x, a.rows, a.cols, a.ld,
-                           sign_mask, a.q, a.s, col_groups);
-    } else {
-        const int64_t bpr = a.cols / 32, nblocks = a.rows * bpr;
-        const unsigned grid = (unsigned)((nblocks + 255) / 256);
-        hipLaunchKernelGGL((quantize_rows_fp8_kernel<HAD>), dim3(grid), dim3(256), 0, st, a.x, nblocks, bpr, a.ld,
-                           (int)(a.ld == a.cols), sign_mask, a.q, a.s);
-    }
-    return hipGetLastError();
-}
-
 template <int HAD>
 hipError_t launch_rows_h(const QuantArgs &a, hipStream_t st)
 {
@@ -712,17 +451,6 @@ hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st)
 }
 
 hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st) { return launch_cols_mode<MODE_COLS>(a, nullptr, st); }
-
-hipError_t launch_quantize_fp8(const QuantArgs &a, bool cols_axis, hipStream_t st)
-{
-    switch (a.hadamard) {
-        case HAD_NONE: return launch_fp8_h<HAD_NONE>(a, cols_axis, st);
-        case HAD_DET: return launch_fp8_h<HAD_DET>(a, cols_axis, st);
-        case HAD_RANDSIGN: return launch_fp8_h<HAD_RANDSIGN>(a, cols_axis, st);
-        case HAD_RANDSIGN16: return launch_fp8_h<HAD_RANDSIGN16>(a, cols_axis, st);
-        default: return launch_fp8_h<HAD_DET16>(a, cols_axis, st);
-    }
-}
 
 hipError_t launch_quantize_dual(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
 {

@@ -173,6 +173,17 @@ int mxfp4_quantize_fp8(const void *x_bf16, int64_t rows, int64_t cols, int64_t l
                        uint64_t seed, void *q8_out, void *s_out, void *hip_stream);
 
 /*
+ * Both MXFP8 quantisations of one tensor from one pass over it (what mxfp4_quantize_dual is for MXFP4): the
+ * row-wise output q8_last [rows][cols], s_last [rows][cols/32] and the column-wise output q8_first [cols][rows],
+ * s_first [cols][rows/32], byte for byte those of two mxfp4_quantize_fp8 calls.
+ *   x bf16 [rows][ld], 16-byte aligned, ld % 8 == 0; rows % 32 == 0, cols % 32 == 0; q pointers 16-byte aligned.
+ * rows == 0 or cols == 0 is a valid empty call.
+ */
+int mxfp4_quantize_fp8_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                            uint64_t seed, void *q8_last, void *s_last, void *q8_first, void *s_first,
+                            void *hip_stream);
+
+/*
  * mxfp4_gemm with each operand in its own element format (mxfp4_format): the same block-scaled matrix
  * instruction takes E2M1 and E4M3 operands in any combination.
  */

@@ -25,7 +25,8 @@ OUT_BF16, OUT_FP32 = 0, 1
 GEOM_1D, GEOM_2D = 0, 1
 FMT_E2M1, FMT_E4M3 = 0, 1
 
-EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_quantize_fp8", "mxfp4_gemm",
+EXPORTS = ("mxfp4_quantize", "mxfp4_quantize_dual", "mxfp4_quantize_2d", "mxfp4_quantize_fp8",
+           "mxfp4_quantize_fp8_dual", "mxfp4_gemm",
            "mxfp4_gemm_fmt", "mxfp4_gemm_pair", "mxfp4_gemm_plan", "mxfp4_linear_fwd", "mxfp4_linear_fwd_static", "mxfp4_linear_bwd",
            "mxfp4_linear_fwd_save", "mxfp4_linear_bwd_saved", "mxfp4_linear_saved_bytes",
            "mxfp4_linear_saved_layout", "mxfp4_linear_workspace_bytes", "mxfp4_linear_workspace_layout",
@@ -64,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.mxfp4_quantize_dual.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp, vp, vp]
         L.mxfp4_quantize_fp8.restype = ci
         L.mxfp4_quantize_fp8.argtypes = [vp, i64, i64, i64, ci, ci, u64, vp, vp, vp]
+        L.mxfp4_quantize_fp8_dual.restype = ci
+        L.mxfp4_quantize_fp8_dual.argtypes = [vp, i64, i64, i64, ci, u64, vp, vp, vp, vp, vp]
         L.mxfp4_gemm_fmt.restype = ci
         L.mxfp4_gemm_fmt.argtypes = [vp, vp, ci, vp, vp, ci, i64, i64, i64, vp, i64, ci, ci, vp]
         L.mxfp4_quantize_2d.restype = ci
@@ -191,6 +194,21 @@ def mxfp4_quantize_fp8(x, axis: int = AXIS_LAST, hadamard: int = HAD_NONE, seed:
     _check("mxfp4_quantize_fp8", lib().mxfp4_quantize_fp8(_ptr(x), rows, cols, ld, axis, hadamard,
                                                           seed & (2**64 - 1), _ptr(q), _ptr(s), _stream_ptr(stream)))
     return q, s
+
+
+def mxfp4_quantize_fp8_dual(x, hadamard: int = HAD_NONE, seed: int = 0, stream=None):
+    """Both MXFP8 quantisations of x [rows][cols] from one pass: returns (q8_last, s_last, q8_first, s_first)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and (x.numel() == 0 or x.stride(1) == 1)
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, x.stride(0))
+    u8 = dict(dtype=torch.uint8, device=x.device)
+    ql, sl = torch.empty((rows, cols), **u8), torch.empty((rows, cols // 32), **u8)
+    qf, sf = torch.empty((cols, rows), **u8), torch.empty((cols, rows // 32), **u8)
+    _check("mxfp4_quantize_fp8_dual", lib().mxfp4_quantize_fp8_dual(_ptr(x), rows, cols, ld, hadamard,
+                                                                    seed & (2**64 - 1), _ptr(ql), _ptr(sl), _ptr(qf),
+                                                                    _ptr(sf), _stream_ptr(stream)))
+    return ql, sl, qf, sf
 
 
 def mxfp4_gemm(a_q, a_s, b_q, b_s, out=None, out_dtype: int = OUT_FP32, accumulate: bool = False, stream=None,

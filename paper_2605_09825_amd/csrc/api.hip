@@ -275,6 +275,25 @@ int mxfp4_quantize_fp8(const void *x_bf16, int64_t rows, int64_t cols, int64_t l
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
+int mxfp4_quantize_fp8_dual(const void *x_bf16, int64_t rows, int64_t cols, int64_t ld_elems, int hadamard,
+                            uint64_t seed, void *q8_last, void *s_last, void *q8_first, void *s_first,
+                            void *hip_stream)
+{
+    // the union of the two single-axis argument rules
+    int rc = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_LAST, hadamard, MXFP4_RNE, q8_last, s_last);
+    int rc2 = check_quantize(x_bf16, rows, cols, ld_elems, MXFP4_AXIS_FIRST, hadamard, MXFP4_RNE, q8_first, s_first);
+    if (rc > 0) return rc;
+    if (rc2 > 0) return rc2;
+    if (rc == 0 || rc2 == 0) return MXFP4_OK;
+    if (!device_ok()) return MXFP4_EDEVICE;
+    QuantArgs a{static_cast<const uint16_t *>(x_bf16), rows, cols, ld_elems, hadamard, MXFP4_RNE, seed,
+                static_cast<uint8_t *>(q8_first), static_cast<uint8_t *>(s_first)};
+    a.q_row = static_cast<uint8_t *>(q8_last);
+    a.s_row = static_cast<uint8_t *>(s_last);
+    hipError_t e = launch_quantize_fp8_dual(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
 int mxfp4_gemm_fmt(const void *a_q, const void *a_s, int a_format, const void *b_q, const void *b_s, int b_format,
                    int64_t R_a, int64_t R_b, int64_t C, void *out, int64_t ld_out, int out_dtype, int accumulate,
                    void *hip_stream)
@@ -366,6 +385,9 @@ static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t 
                             uint8_t *q_first, uint8_t *s_first, void *hip_stream)
 {
     const uint64_t seed_last = operand_seed(cfg, st_last), seed_first = operand_seed(cfg, st_first);
+    if (q_last && q_first && fmt_last == MXFP4_FMT_E4M3 && fmt_first == MXFP4_FMT_E4M3)  // both in 8 bits: one pass
+        return mxfp4_quantize_fp8_dual(x, rows, cols, cols, MXFP4_HAD_NONE, seed_last, q_last, s_last, q_first, s_first,
+                                       hip_stream);
     if (q_last && fmt_last == MXFP4_FMT_E4M3) {
         int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_LAST, MXFP4_HAD_NONE, seed_last, q_last, s_last,
                                     hip_stream);

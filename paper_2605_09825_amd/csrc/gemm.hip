@@ -755,18 +755,19 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const TileGemm p)
 // the 8B shapes this only gains the dispatch gap between two launches (about 6 us): with half the chip idle
 // in a partly filled last round the busy half clocks higher under the power cap, and here each XCD's L2
 // holds panels of two problems (22 % more traffic beyond L2).
-template <bool OUT0, bool OUT1, bool ACC1>
+// FMT0, FMT1: element format of each problem's operands (0 = E2M1, 1 = E4M3), as in gemm_tile_kernel.
+template <bool OUT0, bool OUT1, bool ACC1, int FMT0, int FMT1>
 __global__ __launch_bounds__(256, 1) void gemm_tile_pair_kernel(const TileGemm p0, const TileGemm p1, const int n0)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const uint32_t xcd = blockIdx.x & 7, lw = blockIdx.x >> 3;
     if (lw < (uint32_t)n0)
-        gemm_tile_body<OUT0, false, 0, 4>(p0.aq, p0.as, p0.bq, p0.bs, p0.C, p0.out, p0.ld, p0.tiles_m, p0.tiles_n,
-                                    lw * 8 + xcd, (uint32_t)n0 * 8, smem, lds0);
+        gemm_tile_body<OUT0, false, FMT0, 4>(p0.aq, p0.as, p0.bq, p0.bs, p0.C, p0.out, p0.ld, p0.tiles_m, p0.tiles_n,
+                                             lw * 8 + xcd, (uint32_t)n0 * 8, smem, lds0);
     else
-        gemm_tile_body<OUT1, ACC1, 0, 4>(p1.aq, p1.as, p1.bq, p1.bs, p1.C, p1.out, p1.ld, p1.tiles_m, p1.tiles_n,
-                                   (lw - n0) * 8 + xcd, (uint32_t)(32 - n0) * 8, smem, lds0);
+        gemm_tile_body<OUT1, ACC1, FMT1, 4>(p1.aq, p1.as, p1.bq, p1.bs, p1.C, p1.out, p1.ld, p1.tiles_m, p1.tiles_n,
+                                            (lw - n0) * 8 + xcd, (uint32_t)(32 - n0) * 8, smem, lds0);
 }
 
 }  // namespace
@@ -933,27 +934,39 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
 hipError_t launch_gemm_pair(const GemmArgs &g0, const GemmArgs &g1, hipStream_t st)
 {
     // (the split below counts on 8 XCDs of 32 compute units each)
-    const bool side_by_side = !g0.accumulate && g0.a_fmt == 0 && g1.a_fmt == 0 && tile_eligible(g0) &&
-                              tile_eligible(g1) && device_cus() == NUM_CUS;
+    // Formats: both problems MXFP4 (every combination of output types); or the second, or both, MXFP8 with the
+    // output types of a backward pass (bf16 from problem 0, fp32 from problem 1): the stage-wise recipes of Table 1.
+    const bool fmt_ok = g0.a_fmt == g0.b_fmt && g1.a_fmt == g1.b_fmt && (g0.a_fmt == 0 || g1.a_fmt == 1) &&
+                        (g1.a_fmt == 0 || (!g0.out_fp32 && g1.out_fp32));
+    const bool side_by_side = !g0.accumulate && fmt_ok && tile_eligible(g0) && tile_eligible(g1) &&
+                              device_cus() == NUM_CUS;
     if (side_by_side) {
         const TileGemm p0 = tile_args(g0), p1 = tile_args(g1);
         const int64_t t0 = (int64_t)p0.tiles_m * p0.tiles_n, t1 = (int64_t)p1.tiles_m * p1.tiles_n;
-        const double w0 = (double)t0 * (double)g0.C, w1 = (double)t1 * (double)g1.C;
+        // (an E4M3 element costs the matrix unit twice the time of an E2M1 element)
+        const double w0 = (double)t0 * (double)g0.C * (g0.a_fmt ? 2.0 : 1.0);
+        const double w1 = (double)t1 * (double)g1.C * (g1.a_fmt ? 2.0 : 1.0);
         int n0 = (int)(32.0 * w0 / (w0 + w1) + 0.5);  // workgroups per XCD for g0, in proportion to the work
         n0 = n0 < 1 ? 1 : (n0 > 31 ? 31 : n0);
         // worth it only if both shares have enough tiles to keep their CUs busy
         if (t0 >= (int64_t)n0 * 8 && t1 >= (int64_t)(32 - n0) * 8) {
             dim3 grid(NUM_CUS);
-#define MXFP4_PAIR(O0, O1, A1) \
-    hipLaunchKernelGGL((gemm_tile_pair_kernel<O0, O1, A1>), grid, dim3(256), 0, st, p0, p1, n0)
-            if (g0.out_fp32) {
-                if (!g1.out_fp32) MXFP4_PAIR(true, false, false);
-                else if (g1.accumulate) MXFP4_PAIR(true, true, true);
-                else MXFP4_PAIR(true, true, false);
+#define MXFP4_PAIR(O0, O1, A1, F0, F1) \
+    hipLaunchKernelGGL((gemm_tile_pair_kernel<O0, O1, A1, F0, F1>), grid, dim3(256), 0, st, p0, p1, n0)
+            if (g1.a_fmt) {
+                if (g0.a_fmt) {
+                    if (g1.accumulate) MXFP4_PAIR(false, true, true, 1, 1); else MXFP4_PAIR(false, true, false, 1, 1);
+                } else {
+                    if (g1.accumulate) MXFP4_PAIR(false, true, true, 0, 1); else MXFP4_PAIR(false, true, false, 0, 1);
+                }
+            } else if (g0.out_fp32) {
+                if (!g1.out_fp32) MXFP4_PAIR(true, false, false, 0, 0);
+                else if (g1.accumulate) MXFP4_PAIR(true, true, true, 0, 0);
+                else MXFP4_PAIR(true, true, false, 0, 0);
             } else {
-                if (!g1.out_fp32) MXFP4_PAIR(false, false, false);
-                else if (g1.accumulate) MXFP4_PAIR(false, true, true);
-                else MXFP4_PAIR(false, true, false);
+                if (!g1.out_fp32) MXFP4_PAIR(false, false, false, 0, 0);
+                else if (g1.accumulate) MXFP4_PAIR(false, true, true, 0, 0);
+                else MXFP4_PAIR(false, true, false, 0, 0);
             }
 #undef MXFP4_PAIR
             return hipGetLastError();

@@ -36,6 +36,8 @@ hipError_t launch_quantize_2d(const QuantArgs &a, const QuantArgs *b, hipStream_
 // MXFP8 (E4M3) output, round to nearest even: q[R][C] one byte per element, s[R][C/32]; cols_axis selects the
 // column-wise (32x1, transposed output) layout
 hipError_t launch_quantize_fp8(const QuantArgs &a, bool cols_axis, hipStream_t st);
+// both MXFP8 layouts from one pass over x: q, s column-wise (q[cols][rows]); q_row, s_row row-wise (q_row[rows][cols])
+hipError_t launch_quantize_fp8_dual(const QuantArgs &a, hipStream_t st);
 
 struct GemmArgs {
     const uint8_t *aq, *as, *bq, *bs;

@@ -120,6 +120,114 @@ __global__ __launch_bounds__(512) void quantize_cols_fp8_kernel(const uint16_t *
     }
 }
 
+// both layouts from one pass over the tensor: the tile and the parking scheme of the dual-axis MXFP4 kernel.
+// Each wave parks its 32 x 128 elements in its own LDS slice (the first 16 rows are parked and worked on while
+// the other 16 are still in flight), reads them back as row blocks, two per lane and four lanes per row, so that
+// a row of the tile leaves as 128 contiguous bytes, and then reuses the slice to regroup its column-wise codes:
+// wave w keeps the low 16 bytes of every column's 32 at w * SKEW into its slice and the high 16 bytes FP8_HALF
+// further on, which lets the 16 lanes that later gather one output row's 256 bytes from the 8 slices hit every
+// bank once.
+constexpr int FP8_SLICE = 32 * RAW_PITCH, FP8_HALF = (CT_COLS + 1) * 16, FP8_SKEW = 32;
+static_assert(2 * FP8_HALF + (CT_RB - 1) * FP8_SKEW <= FP8_SLICE, "the codes of a wave must fit its slice");
+
+template <int HAD>
+__global__ __launch_bounds__(512) void quantize_dual_fp8_kernel(const uint16_t *__restrict__ x, int64_t rows,
+                                                                int64_t cols, int64_t ld, uint32_t sign_mask,
+                                                                uint8_t *__restrict__ q, uint8_t *__restrict__ s,
+                                                                uint8_t *__restrict__ q_row,
+                                                                uint8_t *__restrict__ s_row, uint32_t col_groups,
+                                                                int s_row_vec4)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[CT_RB * FP8_SLICE + CT_COLS * CT_RB];
+    uint8_t(*lds_s)[CT_RB] = reinterpret_cast<uint8_t(*)[CT_RB]>(lds + CT_RB * FP8_SLICE);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t by = blockIdx.x / col_groups, bx = blockIdx.x - by * col_groups;
+    const int64_t c0 = (int64_t)bx * CT_COLS, rb0 = (int64_t)by * CT_RB, nrb = rows >> 5;
+    const int64_t rb = rb0 + w, col = c0 + 2 * lane;
+    uint32_t raw[32];
+    if ((rb < nrb) && (col < cols)) {
+        const uint16_t *p = x + (rb * 32) * ld + col;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) raw[i] = *reinterpret_cast<const uint32_t *>(p + i * ld);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) raw[i] = 0;
+    }
+
+    // ---- row-wise output ----
+    uint8_t *mine = lds + w * FP8_SLICE;
+    const int cb = lane & 3;
+    const int64_t colb = c0 + 32 * cb, bpr = cols >> 5;
+    const bool on = (rb < nrb) && (colb < cols);
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+        for (int i = 16 * pass; i < 16 * pass + 16; ++i)
+            *reinterpret_cast<uint32_t *>(mine + i * RAW_PITCH + 4 * lane) = raw[i];
+        wave_sync();  // (the slice is written and read by this wave only)
+        const int r = (lane >> 2) + 16 * pass;
+        const uint4 *p = reinterpret_cast<const uint4 *>(mine + r * RAW_PITCH + 64 * cb);
+        uint4 rraw[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rraw[j] = p[j];
+        float v[32];
+        widen(rraw, v);
+        rotate_block<HAD>(v, sign_mask);
+        uint4 lo, hi;
+        uint32_t sb;
+        encode_scaled_fp8(v, amax_bits(v), lo, hi, sb);
+        const int64_t g = (rb * 32 + r) * bpr + (colb >> 5);
+        if (on) {
+            reinterpret_cast<uint4 *>(q_row)[2 * g] = lo;
+            reinterpret_cast<uint4 *>(q_row)[2 * g + 1] = hi;
+        }
+        // the four scale bytes of one row of the tile go out as one dword where they can
+        uint32_t s4 = sb;
+        s4 |= (uint32_t)__shfl_down((int)sb, 1) << 8;
+        s4 |= (uint32_t)__shfl_down((int)sb, 2) << 16;
+        s4 |= (uint32_t)__shfl_down((int)sb, 3) << 24;
+        if (s_row_vec4 && c0 + CT_COLS <= cols) {
+            if (on && cb == 0) *reinterpret_cast<uint32_t *>(s_row + g) = s4;
+        } else if (on) {
+            s_row[g] = (uint8_t)sb;
+        }
+        __builtin_amdgcn_sched_barrier(0);  // (keep the second half's LDS writes, and with them the wait, down here)
+    }
+    wave_sync();  // the wave is done with its parked elements: the slice becomes its regrouping buffer
+
+    // ---- column-wise output ----
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        float v[32];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = j == 0 ? bf16_lo(raw[i]) : bf16_hi(raw[i]);
+        rotate_block<HAD>(v, sign_mask);
+        uint4 lo, hi;
+        uint32_t sb;
+        encode_scaled_fp8(v, amax_bits(v), lo, hi, sb);
+        uint8_t *base = mine + w * FP8_SKEW;
+        reinterpret_cast<uint4 *>(base)[2 * lane + j] = lo;
+        reinterpret_cast<uint4 *>(base + FP8_HALF)[2 * lane + j] = hi;
+        lds_s[2 * lane + j][w] = (uint8_t)sb;
+    }
+    // workgroup barrier for the LDS traffic only (it does not wait for the row-wise stores still in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // 16 consecutive threads write the 256 bytes one output row receives from this tile
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int idx = pass * 512 + tid, cl = idx >> 4, k = idx & 15, b = k >> 1, half = k & 1;
+        if (c0 + cl < cols && rb0 + b < nrb)
+            *reinterpret_cast<uint4 *>(q + (c0 + cl) * rows + (rb0 + b) * 32 + half * 16) =
+                *reinterpret_cast<const uint4 *>(lds + b * (FP8_SLICE + FP8_SKEW) + half * FP8_HALF + cl * 16);
+    }
+    if (tid < CT_COLS && c0 + tid < cols) {
+        uint8_t *dst = s + (c0 + tid) * nrb + rb0;
+#pragma unroll
+        for (int k = 0; k < CT_RB; ++k)
+            if (rb0 + k < nrb) dst[k] = lds_s[tid][k];
+    }
+}
+
 template <int HAD>
 hipError_t launch_fp8_h(const QuantArgs &a, bool cols_axis, hipStream_t st)
 {
@@ -139,7 +247,30 @@ hipError_t launch_fp8_h(const QuantArgs &a, bool cols_axis, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int HAD>
+hipError_t launch_fp8_dual_h(const QuantArgs &a, hipStream_t st)
+{
+    const int64_t nrb = a.rows / 32;
+    const uint32_t col_groups = (uint32_t)((a.cols + CT_COLS - 1) / CT_COLS);
+    dim3 grid((unsigned)(col_groups * ((nrb + CT_RB - 1) / CT_RB)));
+    const int s_row_vec4 = (((a.cols / 32) % 4) == 0) && ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
+    hipLaunchKernelGGL((quantize_dual_fp8_kernel<HAD>), grid, dim3(512), 0, st, a.x, a.rows, a.cols, a.ld,
+                       sign_mask_of(a.seed), a.q, a.s, a.q_row, a.s_row, col_groups, s_row_vec4);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_quantize_fp8_dual(const QuantArgs &a, hipStream_t st)
+{
+    switch (a.hadamard) {
+        case HAD_NONE: return launch_fp8_dual_h<HAD_NONE>(a, st);
+        case HAD_DET: return launch_fp8_dual_h<HAD_DET>(a, st);
+        case HAD_RANDSIGN: return launch_fp8_dual_h<HAD_RANDSIGN>(a, st);
+        case HAD_RANDSIGN16: return launch_fp8_dual_h<HAD_RANDSIGN16>(a, st);
+        default: return launch_fp8_dual_h<HAD_DET16>(a, st);
+    }
+}
 
 hipError_t launch_quantize_fp8(const QuantArgs &a, bool cols_axis, hipStream_t st)
 {

@@ -66,6 +66,17 @@ def test_quantize_argument_errors(L):
     assert q(None, 0, 64, 64, 0, 0, 0, 0, None, None, None) == mx.OK      # empty
 
 
+def test_quantize_fp8_dual_argument_errors(L):
+    d = L.mxfp4_quantize_fp8_dual
+    assert d(P, 64, 64, 64, 9, 0, P, P, P, P, None) == mx.EINVAL          # hadamard
+    assert d(P, 64, 64, 64, 0, 0, P, P, None, P, None) == mx.EINVAL
+    assert d(P, 64, 48, 64, 0, 0, P, P, P, P, None) == mx.ESHAPE          # cols % 32
+    assert d(P, 48, 64, 64, 0, 0, P, P, P, P, None) == mx.ESHAPE          # rows % 32
+    assert d(P, 64, 64, 68, 0, 0, P, P, P, P, None) == mx.EALIGN          # ld % 8
+    assert d(P, 64, 64, 64, 0, 0, P + 8, P, P, P, None) == mx.EALIGN
+    assert d(None, 0, 64, 64, 0, 0, None, None, None, None, None) == mx.OK  # empty
+
+
 def test_gemm_argument_errors(L):
     g = L.mxfp4_gemm
     assert g(P, P, P, P, 16, 16, 32, P, 16, 5, 0, None) == mx.EINVAL      # dtype

@@ -12,7 +12,7 @@ import oracle
 import paper_2605_09825_amd as mx
 from paper_2605_09825_amd import synth
 from gpu_util import first_mismatch
-from test_gpu_gemm import assert_close, gpu
+from test_gpu_gemm import assert_close, close_bf16, gpu, structured_check
 
 pytestmark = pytest.mark.gpu
 FP8_RTOL = 7 * 2.0 ** -13 + 1e-5
@@ -39,6 +39,35 @@ def test_rows(shape, had):
 @pytest.mark.parametrize("shape", [(256, 128), (96, 74), (32, 2), (288, 130), (1056, 258), (512, 1024)])
 def test_cols(shape, had):
     check_q(synth.student_t3(shape[0], shape[1], 1.0, 4, synth.STREAM_DY), mx.AXIS_FIRST, had, seed=12)
+
+
+@pytest.mark.parametrize("had", HADS)
+@pytest.mark.parametrize("shape", [(256, 128), (32, 32), (96, 160), (288, 416), (1056, 2080), (2048, 1024)])
+def test_dual_axis_call_equals_the_oracle_on_both_outputs(shape, had):
+    # one pass over the tensor, both MXFP8 layouts (ragged tiles: rows not in whole 256s, columns not in whole 128s)
+    t = synth.student_t3(shape[0], shape[1], 1.0, 6, synth.STREAM_DY)
+    xb = synth.as_u16(t)
+    ql, sl, qf, sf = mx.mxfp4_quantize_fp8_dual(t.to("cuda:0"), had, seed=13)
+    torch.cuda.synchronize()
+    for axis, q, s_ in ((mx.AXIS_LAST, ql, sl), (mx.AXIS_FIRST, qf, sf)):
+        qo, so = oracle.quantize_fp8(xb, axis, had, 13)
+        assert np.array_equal(s_.cpu().numpy(), so), f"axis {axis} scales: " + first_mismatch(s_.cpu().numpy(), so)
+        assert np.array_equal(q.cpu().numpy(), qo), f"axis {axis} codes: " + first_mismatch(q.cpu().numpy(), qo)
+
+
+def test_dual_axis_call_on_a_strided_view_and_special_values():
+    u = synth.as_u16(synth.normal(96, 320, 1.0, 8, synth.STREAM_X)).copy()
+    u[5, 40] = 0x7F80            # +inf
+    u[70, 200] = 0x7FC1          # a NaN
+    u[33, 64:96] = 0             # an all-zero block
+    big = synth.from_bits(u)
+    xb = u[:, 32:288]            # ld = 320, cols = 256
+    ql, sl, qf, sf = mx.mxfp4_quantize_fp8_dual(big.to("cuda:0")[:, 32:288], mx.HAD_DET)
+    torch.cuda.synchronize()
+    for axis, q, s_ in ((mx.AXIS_LAST, ql, sl), (mx.AXIS_FIRST, qf, sf)):
+        qo, so = oracle.quantize_fp8(xb, axis, mx.HAD_DET, 0)
+        assert np.array_equal(s_.cpu().numpy(), so) and np.array_equal(q.cpu().numpy(), qo)
+        assert (so == 0xFF).sum() >= 2
 
 
 @pytest.mark.parametrize("axis", [mx.AXIS_LAST, mx.AXIS_FIRST])
@@ -232,6 +261,39 @@ def test_linear_with_stage_formats(shape, fmts, saved_path):
         o, absum = oracle.gemm_fmt(want[a][0], want[a][1], f, want[b][0], want[b][1], f)
         tol = FP8_RTOL if f else 1e-5
         assert np.all(np.abs(out.cpu().numpy() - o) <= tol * absum), (a, b)
+
+
+@pytest.mark.parametrize("fmts", [(0, 1, 1), (0, 0, 1)])
+def test_backward_side_by_side_launch_with_mxfp8_stages(fmts):
+    # M = N = K = 4096: Dgrad and Wgrad have 256 tiles each, enough for the launch that runs them side by side
+    # (bf16 dX, fp32 dW), with Dgrad in MXFP8 or MXFP4 and Wgrad in MXFP8.  Bit-equal to each gradient asked for
+    # alone (launches of their own), and against the oracle on a patch in every tile plus whole rows and columns.
+    M = N = K = 4096
+    fF, fD, fW = fmts
+    x = synth.normal(M, K, 1.0, 2, synth.STREAM_X)
+    w = synth.normal(N, K, 0.02, 2, synth.STREAM_W)
+    dy = synth.normal(M, N, 1e-3, 2, synth.STREAM_DY)
+    cfg = mx.make_cfg(mx.HAD_DET, mx.RNE, 5, y_dtype=mx.OUT_BF16, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32,
+                      fprop_format=fF, dgrad_format=fD, wgrad_format=fW)
+    xg, wg, dyg = x.to("cuda:0"), w.to("cuda:0"), dy.to("cuda:0")
+    dx, dw, ws_b = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg)
+    dx1, _, _ = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg, need_dw=False)
+    _, dw1, _ = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg, need_dx=False)
+    torch.cuda.synchronize()
+    assert torch.equal(dx, dx1) and torch.equal(dw, dw1)
+    ops = _slices(ws_b, mx.mxfp4_linear_workspace_layout(M, N, K, True, cfg), [(M, N), (K, N), (N, M), (K, M)],
+                  [fD, fD, fW, fW])
+    rng = np.random.default_rng(4)
+
+    def close_fp8_bf16(got, want, absum):
+        assert (np.abs(got - want) <= FP8_RTOL * absum + 2.0**-8 * np.abs(want)).all()
+
+    def close_fp8(got, want, absum):
+        assert (np.abs(got - want) <= FP8_RTOL * absum).all()
+    structured_check(dx.float().cpu().numpy().astype(np.float64), ops[0], ops[1], rng, fmts=(fD, fD), n_lines=16,
+                     close=close_fp8_bf16 if fD else close_bf16)
+    structured_check(dw.cpu().numpy().astype(np.float64), ops[2], ops[3], rng, fmts=(fW, fW), n_lines=16,
+                     close=close_fp8)
 
 
 def test_stage_formats_reject_2d_geometry():

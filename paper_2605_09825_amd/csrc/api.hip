@@ -388,6 +388,17 @@ static int quantize_operand(const mxfp4_linear_cfg *cfg, const void *x, int64_t 
     if (q_last && q_first && fmt_last == MXFP4_FMT_E4M3 && fmt_first == MXFP4_FMT_E4M3)  // both in 8 bits: one pass
         return mxfp4_quantize_fp8_dual(x, rows, cols, cols, MXFP4_HAD_NONE, seed_last, q_last, s_last, q_first, s_first,
                                        hip_stream);
+    if (q_last && q_first && fmt_last == MXFP4_FMT_E2M1 && fmt_first == MXFP4_FMT_E4M3 &&
+        cfg->geometry == MXFP4_GEOM_1D) {
+        // row-wise MXFP4 and column-wise MXFP8 (the stage-wise recipes between "Fprop only" and "all three"): one pass
+        QuantArgs a;
+        int rc = prep_dual(x, rows, cols, cols, cfg->hadamard, cfg->rounding, seed_last, seed_first, q_last, s_last,
+                           q_first, s_first, a);
+        if (rc >= 0) return rc;
+        if (!device_ok()) return MXFP4_EDEVICE;
+        hipError_t e = launch_quantize_mxfp4_rows_mxfp8_cols(a, static_cast<hipStream_t>(hip_stream));
+        return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+    }
     if (q_last && fmt_last == MXFP4_FMT_E4M3) {
         int rc = mxfp4_quantize_fp8(x, rows, cols, cols, MXFP4_AXIS_LAST, MXFP4_HAD_NONE, seed_last, q_last, s_last,
                                     hip_stream);

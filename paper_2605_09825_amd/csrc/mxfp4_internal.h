@@ -38,6 +38,10 @@ hipError_t launch_quantize_2d(const QuantArgs &a, const QuantArgs *b, hipStream_
 hipError_t launch_quantize_fp8(const QuantArgs &a, bool cols_axis, hipStream_t st);
 // both MXFP8 layouts from one pass over x: q, s column-wise (q[cols][rows]); q_row, s_row row-wise (q_row[rows][cols])
 hipError_t launch_quantize_fp8_dual(const QuantArgs &a, hipStream_t st);
+// one pass over x for a tensor that feeds one MXFP4 and one MXFP8 GEMM: q_row, s_row = the row-wise MXFP4 output
+// (rotation a.hadamard, rounding a.rounding under a.seed_row; the sign diagonal from a.seed), q, s = the column-wise
+// MXFP8 output (unrotated, round to nearest)
+hipError_t launch_quantize_mxfp4_rows_mxfp8_cols(const QuantArgs &a, hipStream_t st);
 
 struct GemmArgs {
     const uint8_t *aq, *as, *bq, *bs;

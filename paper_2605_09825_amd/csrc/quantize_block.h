@@ -127,6 +127,62 @@ __device__ __forceinline__ void widen(const uint4 (&raw)[4], float (&v)[32])
     }
 }
 
+// FP4 codes of one rotated block under the scale that follows from the shared maximum `amax` (bit
+// pattern): eq. (1) with the OCP scale rule.  idx0: linear index of element 0 in the quantised output
+// (stochastic rounding counter).
+template <int RND>
+__device__ __forceinline__ void encode_scaled(const float (&v)[32], uint32_t amax, RngKey key, uint64_t idx0,
+                                              uint4 &codes, uint32_t &scale_byte)
+{
+    uint32_t eb = amax >> 23;
+    bool bad = (eb == 255u);
+    uint32_t sb = eb > 2u ? eb - 2u : 0u;  // eb <= 254 here, so sb <= 252
+    scale_byte = bad ? 0xFFu : sb;
+
+    uint32_t w[4];
+    if (RND == RND_RNE) {
+        // The converter divides by 2^(exponent field of `scale` - 127), rounds to nearest
+        // even on the E2M1 grid and saturates at 6; it writes one byte (two codes) per issue.
+        float scale = __uint_as_float(sb << 23);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t r = 0;
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 0], v[8 * j + 1], scale, 0);
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 2], v[8 * j + 3], scale, 1);
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 4], v[8 * j + 5], scale, 2);
+            r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, v[8 * j + 6], v[8 * j + 7], scale, 3);
+            w[j] = r;
+        }
+    } else {
+        float inv = __uint_as_float((254u - sb) << 23);  // 2^-(sb-127); field in [2,254]
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t r = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int i = 8 * j + e;
+                uint32_t code = sr_code(v[i] * inv, rand32(key, idx0 + (uint64_t)i));
+                r |= code << (4 * e);
+            }
+            w[j] = r;
+        }
+    }
+    codes = bad ? make_uint4(0, 0, 0, 0) : make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Code store.  streaming: for tensors larger than the 256 MB last-level cache the output cannot stay cached
+// for the GEMM anyway, and marking the stores non-temporal is worth 3-8 % there (measured); smaller tensors
+// keep ordinary stores so that the GEMM finds its operands in cache.
+__device__ __forceinline__ void store_codes(uint4 *p, uint4 v, int streaming)
+{
+    if (streaming) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+    } else {
+        *p = v;
+    }
+}
+
 // ---- column-wise workgroup tile: 256 rows (8 row blocks, one per wave) x 128 columns (2 per lane) ----
 constexpr int CT_COLS = 128, CT_RB = 8;
 constexpr int RAW_PITCH = 272;  // bytes per parked row: 256 + 16, so that the 16-byte reads below (16 lanes =

@@ -130,13 +130,16 @@ __global__ __launch_bounds__(512) void quantize_cols_fp8_kernel(const uint16_t *
 constexpr int FP8_SLICE = 32 * RAW_PITCH, FP8_HALF = (CT_COLS + 1) * 16, FP8_SKEW = 32;
 static_assert(2 * FP8_HALF + (CT_RB - 1) * FP8_SKEW <= FP8_SLICE, "the codes of a wave must fit its slice");
 
-template <int HAD>
+// ROW4: the row-wise output is MXFP4 instead (rotation HAD_ROW, rounding RND_ROW under key_row: what the MXFP4
+// kernels write), the column-wise one stays MXFP8 under rotation HAD: a tensor that feeds one MXFP4 and one MXFP8
+// GEMM of the stage-wise recipe (X and W when only Fprop is in MXFP4, X and dY when Fprop and Dgrad are).
+template <int HAD, bool ROW4, int HAD_ROW, int RND_ROW>
 __global__ __launch_bounds__(512) void quantize_dual_fp8_kernel(const uint16_t *__restrict__ x, int64_t rows,
                                                                 int64_t cols, int64_t ld, uint32_t sign_mask,
                                                                 uint8_t *__restrict__ q, uint8_t *__restrict__ s,
                                                                 uint8_t *__restrict__ q_row,
                                                                 uint8_t *__restrict__ s_row, uint32_t col_groups,
-                                                                int s_row_vec4)
+                                                                int s_row_vec4, RngKey key_row)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[CT_RB * FP8_SLICE + CT_COLS * CT_RB];
     uint8_t(*lds_s)[CT_RB] = reinterpret_cast<uint8_t(*)[CT_RB]>(lds + CT_RB * FP8_SLICE);
@@ -172,14 +175,21 @@ __global__ __launch_bounds__(512) void quantize_dual_fp8_kernel(const uint16_t *
         for (int j = 0; j < 4; ++j) rraw[j] = p[j];
         float v[32];
         widen(rraw, v);
-        rotate_block<HAD>(v, sign_mask);
-        uint4 lo, hi;
+        const int64_t row = rb * 32 + r, g = row * bpr + (colb >> 5);
         uint32_t sb;
-        encode_scaled_fp8(v, amax_bits(v), lo, hi, sb);
-        const int64_t g = (rb * 32 + r) * bpr + (colb >> 5);
-        if (on) {
-            reinterpret_cast<uint4 *>(q_row)[2 * g] = lo;
-            reinterpret_cast<uint4 *>(q_row)[2 * g + 1] = hi;
+        if constexpr (ROW4) {
+            rotate_block<HAD_ROW>(v, sign_mask);
+            uint4 codes;
+            encode_scaled<RND_ROW>(v, amax_bits(v), key_row, (uint64_t)row * (uint64_t)cols + (uint64_t)colb, codes, sb);
+            if (on) reinterpret_cast<uint4 *>(q_row)[g] = codes;
+        } else {
+            rotate_block<HAD>(v, sign_mask);
+            uint4 lo, hi;
+            encode_scaled_fp8(v, amax_bits(v), lo, hi, sb);
+            if (on) {
+                reinterpret_cast<uint4 *>(q_row)[2 * g] = lo;
+                reinterpret_cast<uint4 *>(q_row)[2 * g + 1] = hi;
+            }
         }
         // the four scale bytes of one row of the tile go out as one dword where they can
         uint32_t s4 = sb;
@@ -247,16 +257,24 @@ hipError_t launch_fp8_h(const QuantArgs &a, bool cols_axis, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int HAD>
+template <int HAD, bool ROW4, int HAD_ROW, int RND_ROW>
 hipError_t launch_fp8_dual_h(const QuantArgs &a, hipStream_t st)
 {
     const int64_t nrb = a.rows / 32;
     const uint32_t col_groups = (uint32_t)((a.cols + CT_COLS - 1) / CT_COLS);
     dim3 grid((unsigned)(col_groups * ((nrb + CT_RB - 1) / CT_RB)));
     const int s_row_vec4 = (((a.cols / 32) % 4) == 0) && ((reinterpret_cast<uintptr_t>(a.s_row) % 4) == 0);
-    hipLaunchKernelGGL((quantize_dual_fp8_kernel<HAD>), grid, dim3(512), 0, st, a.x, a.rows, a.cols, a.ld,
-                       sign_mask_of(a.seed), a.q, a.s, a.q_row, a.s_row, col_groups, s_row_vec4);
+    hipLaunchKernelGGL((quantize_dual_fp8_kernel<HAD, ROW4, HAD_ROW, RND_ROW>), grid, dim3(512), 0, st, a.x, a.rows,
+                       a.cols, a.ld, sign_mask_of(a.seed), a.q, a.s, a.q_row, a.s_row, col_groups, s_row_vec4,
+                       make_key(a.seed_row));
     return hipGetLastError();
+}
+
+template <int HAD_ROW>
+hipError_t launch_mixed_h(const QuantArgs &a, hipStream_t st)
+{
+    return a.rounding == RND_RNE ? launch_fp8_dual_h<HAD_NONE, true, HAD_ROW, RND_RNE>(a, st)
+                                 : launch_fp8_dual_h<HAD_NONE, true, HAD_ROW, RND_SR>(a, st);
 }
 
 }  // namespace
@@ -264,11 +282,22 @@ hipError_t launch_fp8_dual_h(const QuantArgs &a, hipStream_t st)
 hipError_t launch_quantize_fp8_dual(const QuantArgs &a, hipStream_t st)
 {
     switch (a.hadamard) {
-        case HAD_NONE: return launch_fp8_dual_h<HAD_NONE>(a, st);
-        case HAD_DET: return launch_fp8_dual_h<HAD_DET>(a, st);
-        case HAD_RANDSIGN: return launch_fp8_dual_h<HAD_RANDSIGN>(a, st);
-        case HAD_RANDSIGN16: return launch_fp8_dual_h<HAD_RANDSIGN16>(a, st);
-        default: return launch_fp8_dual_h<HAD_DET16>(a, st);
+        case HAD_NONE: return launch_fp8_dual_h<HAD_NONE, false, HAD_NONE, RND_RNE>(a, st);
+        case HAD_DET: return launch_fp8_dual_h<HAD_DET, false, HAD_NONE, RND_RNE>(a, st);
+        case HAD_RANDSIGN: return launch_fp8_dual_h<HAD_RANDSIGN, false, HAD_NONE, RND_RNE>(a, st);
+        case HAD_RANDSIGN16: return launch_fp8_dual_h<HAD_RANDSIGN16, false, HAD_NONE, RND_RNE>(a, st);
+        default: return launch_fp8_dual_h<HAD_DET16, false, HAD_NONE, RND_RNE>(a, st);
+    }
+}
+
+hipError_t launch_quantize_mxfp4_rows_mxfp8_cols(const QuantArgs &a, hipStream_t st)
+{
+    switch (a.hadamard) {
+        case HAD_NONE: return launch_mixed_h<HAD_NONE>(a, st);
+        case HAD_DET: return launch_mixed_h<HAD_DET>(a, st);
+        case HAD_RANDSIGN: return launch_mixed_h<HAD_RANDSIGN>(a, st);
+        case HAD_RANDSIGN16: return launch_mixed_h<HAD_RANDSIGN16>(a, st);
+        default: return launch_mixed_h<HAD_DET16>(a, st);
     }
 }
 

@@ -222,10 +222,11 @@ def _oracle_q(x, axis, fmt, had, rnd, seed):
 
 @pytest.mark.parametrize("saved_path", [False, True])
 @pytest.mark.parametrize("fmts", [(0, 1, 1), (0, 0, 1), (1, 1, 1), (1, 0, 0), (0, 1, 0)])
-@pytest.mark.parametrize("shape", [(256, 512, 1024), (96, 160, 224)])
-def test_linear_with_stage_formats(shape, fmts, saved_path):
+@pytest.mark.parametrize("shape,had,rnd", [((256, 512, 1024), mx.HAD_DET, mx.RNE), ((96, 160, 224), mx.HAD_DET, mx.RNE),
+                                           ((288, 416, 352), mx.HAD_RANDSIGN16, mx.SR)])
+def test_linear_with_stage_formats(shape, had, rnd, fmts, saved_path):
     M, N, K = shape
-    had, rnd, seed = mx.HAD_DET, mx.RNE, 31
+    seed = 31
     fF, fD, fW = fmts
     x = synth.normal(M, K, 1.0, 1, synth.STREAM_X)
     w = synth.normal(N, K, 0.02, 1, synth.STREAM_W)
@@ -242,9 +243,12 @@ def test_linear_with_stage_formats(shape, fmts, saved_path):
     torch.cuda.synchronize()
     xb, wb, dyb = synth.as_u16(x), synth.as_u16(w), synth.as_u16(dy)
     L, F = oracle.AXIS_LAST, oracle.AXIS_FIRST
-    want = {"X": _oracle_q(xb, L, fF, had, rnd, seed), "W": _oracle_q(wb, L, fF, had, rnd, seed),
-            "dY": _oracle_q(dyb, L, fD, had, rnd, seed), "W^T": _oracle_q(wb, F, fD, had, rnd, seed),
-            "dY^T": _oracle_q(dyb, F, fW, had, rnd, seed), "X^T": _oracle_q(xb, F, fW, had, rnd, seed)}
+    sd = lambda stream: oracle.seed_with_stream(seed, stream)   # every operand rounds under its own stream
+    want = {"X": _oracle_q(xb, L, fF, had, rnd, sd(oracle.STREAM_X)), "W": _oracle_q(wb, L, fF, had, rnd, sd(oracle.STREAM_W)),
+            "dY": _oracle_q(dyb, L, fD, had, rnd, sd(oracle.STREAM_DY)),
+            "W^T": _oracle_q(wb, F, fD, had, rnd, sd(oracle.STREAM_WT)),
+            "dY^T": _oracle_q(dyb, F, fW, had, rnd, sd(oracle.STREAM_DYT)),
+            "X^T": _oracle_q(xb, F, fW, had, rnd, sd(oracle.STREAM_XT))}
     fw = _slices(ws_f, mx.mxfp4_linear_workspace_layout(M, N, K, False, cfg), [(M, K), (N, K)], [fF, fF])
     bw = _slices(ws_b, mx.mxfp4_linear_workspace_layout(M, N, K, True, cfg), [(M, N), (K, N), (N, M), (K, M)],
                  [fD, fD, fW, fW])

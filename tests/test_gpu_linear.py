@@ -126,3 +126,35 @@ def test_config2_all_three_stages_every_tile():
     ]
     for out, ((aq, as_), (bq, bs)) in stages:
         structured_check(out.cpu().numpy(), (aq, as_), (bq, bs), rng)
+
+
+def test_calls_enqueue_on_the_stream_they_are_given_and_nowhere_else():
+    # The calls only enqueue on the caller's stream.  A side stream is held busy by a spin kernel, the forward and
+    # backward calls are given that stream while the default stream is current: as long as the spin kernel runs
+    # none of their outputs may have been touched, and once the side stream has drained they must be complete.
+    M, N, K = 512, 768, 1024
+    dev = "cuda:0"
+    cfg = mx.make_cfg(mx.HAD_DET, mx.RNE, 3, y_dtype=mx.OUT_FP32, dx_dtype=mx.OUT_FP32, dw_dtype=mx.OUT_FP32)
+    x = synth.normal(M, K, 1.0, 4, synth.STREAM_X).to(dev)
+    w = synth.normal(N, K, 0.02, 4, synth.STREAM_W).to(dev)
+    dy = synth.normal(M, N, 1e-3, 4, synth.STREAM_DY).to(dev)
+    y_ref, _ = mx.mxfp4_linear_fwd(x, w, cfg)
+    dx_ref, dw_ref, _ = mx.mxfp4_linear_bwd(dy, x, w, cfg)
+    y = torch.full((M, N), 7.0, dtype=torch.float32, device=dev)
+    dx = torch.full((M, K), 7.0, dtype=torch.float32, device=dev)
+    dw = torch.full((N, K), 7.0, dtype=torch.float32, device=dev)
+    ws_f = torch.empty(mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, False), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(mx.mxfp4_linear_workspace_bytes(M, N, K, cfg, True), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        torch.cuda._sleep(int(4e8))   # a bounded spin (a fraction of a second) that keeps the side stream busy
+    mx.mxfp4_linear_fwd(x, w, cfg, y=y, workspace=ws_f, stream=side)
+    mx.mxfp4_linear_bwd(dy, x, w, cfg, dx=dx, dw=dw, workspace=ws_b, stream=side)
+    torch.cuda.current_stream().synchronize()          # whatever went to the default stream has run by now
+    untouched = all(bool((t == 7.0).all()) for t in (y, dx, dw))
+    still_spinning = not side.query()
+    side.synchronize()
+    if still_spinning:
+        assert untouched, "a call ran ahead of the work queued before it on its stream"
+    assert torch.equal(y, y_ref) and torch.equal(dx, dx_ref) and torch.equal(dw, dw_ref)

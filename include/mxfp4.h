@@ -230,12 +230,15 @@ int mxfp4_gemm_pair(const void *a0_q, const void *a0_s, const void *b0_q, const 
  * block-scaled FP4 GEMM (Sec. 2.1) on 256 x 256 tiles or, where those would leave compute units idle, on
  * 256 x 128 tiles, and a slower any-shape kernel for edge strips and for contraction lengths below 1024 or
  * not in whole 256s (MXFP8: 128s).  Host-only: touches no device.
- *   parts[5 * i ..] = kind (0 any-shape, 1 tiled 256 x 256, 2 tiled 256 x 128), first row, rows, first column,
- *   columns of block i of the output; *n_parts <= 4 receives their number (0 for an empty product).
+ *   parts[6 * i ..] = kind, first row, rows, first column, columns of block i of the output, main tiles;
+ *   kind: 0 any-shape, 1 tiled 256 x 256, 2 tiled 256 x 128, 3 one launch that runs `main tiles` tiles (whole
+ *   rounds over the compute units) on 256 x 256 and the rest of the block, a last round at most half full, as
+ *   twice as many 256 x 128 tiles; main tiles is 0 for the other kinds.
+ *   *n_parts <= 4 receives the number of blocks (0 for an empty product).
  * Returns MXFP4_OK, MXFP4_EINVAL or MXFP4_ESHAPE as the GEMM call would.
  */
 int mxfp4_gemm_plan(int64_t R_a, int64_t R_b, int64_t C, int a_format, int b_format, int64_t ld_out,
-                    int compute_units, int *n_parts, int64_t parts[20]);
+                    int compute_units, int *n_parts, int64_t parts[24]);
 
 /*
  * Fprop of one linear layer (App. C.1): Y[M][N] = Q(X H) Q(W H)^T, contraction over K.

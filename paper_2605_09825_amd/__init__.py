@@ -250,17 +250,17 @@ def mxfp4_gemm_pair(a0, b0, out0, a1, b1, out1, accumulate1: bool = False, strea
     return out0, out1
 
 
-GEMM_ANY, GEMM_TILED_256, GEMM_TILED_128 = 0, 1, 2
+GEMM_ANY, GEMM_TILED_256, GEMM_TILED_128, GEMM_TILED_256_TAIL_128 = 0, 1, 2, 3
 
 
 def mxfp4_gemm_plan(Ra: int, Rb: int, C: int, a_format: int = FMT_E2M1, b_format: int = FMT_E2M1,
                     ld_out: Optional[int] = None, compute_units: int = 256):
-    """The kernels a GEMM of this shape is cut into: list of (kind, r0, rows, c0, cols).  Host-only."""
+    """The kernels a GEMM of this shape is cut into: list of (kind, r0, rows, c0, cols, main_tiles).  Host-only."""
     n = ctypes.c_int(0)
-    parts = (ctypes.c_int64 * 20)()
+    parts = (ctypes.c_int64 * 24)()
     _check("mxfp4_gemm_plan", lib().mxfp4_gemm_plan(Ra, Rb, C, a_format, b_format, Rb if ld_out is None else ld_out,
                                                     compute_units, ctypes.byref(n), parts))
-    return [tuple(int(parts[5 * i + k]) for k in range(5)) for i in range(n.value)]
+    return [tuple(int(parts[6 * i + k]) for k in range(6)) for i in range(n.value)]
 
 
 def mxfp4_linear_workspace_bytes(M: int, N: int, K: int, cfg: LinearCfg, bwd: bool) -> int:

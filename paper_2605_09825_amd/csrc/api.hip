@@ -339,7 +339,7 @@ int mxfp4_gemm_pair(const void *a0_q, const void *a0_s, const void *b0_q, const 
 }
 
 int mxfp4_gemm_plan(int64_t R_a, int64_t R_b, int64_t C, int a_format, int b_format, int64_t ld_out,
-                    int compute_units, int *n_parts, int64_t parts[20])
+                    int compute_units, int *n_parts, int64_t parts[24])
 {
     if (!n_parts || !parts || compute_units <= 0) return MXFP4_EINVAL;
     if ((a_format != MXFP4_FMT_E2M1 && a_format != MXFP4_FMT_E4M3) ||
@@ -353,8 +353,8 @@ int mxfp4_gemm_plan(int64_t R_a, int64_t R_b, int64_t C, int a_format, int b_for
     const GemmPlan plan = plan_gemm(g, compute_units);
     for (int i = 0; i < plan.n; ++i) {
         const GemmPart &p = plan.part[i];
-        const int64_t row[5] = {p.kind, p.r0, p.rows, p.c0, p.cols};
-        memcpy(parts + 5 * i, row, sizeof(row));
+        const int64_t row[6] = {p.kind, p.r0, p.rows, p.c0, p.cols, p.main_tiles};
+        memcpy(parts + 6 * i, row, sizeof(row));
     }
     *n_parts = plan.n;
     return MXFP4_OK;

@@ -218,13 +218,19 @@ struct TileSrc {
 // instructions per K-step).  2 (E2M1 only): a 256 x 128 tile (sub-tile 128 x 64, 8 instructions per K-step) for
 // outputs that have too few 256 x 256 tiles to fill the chip, and for the part-filled last round of others;
 // it moves 1.5 times the operand bytes per flop, so it is only used where compute units would idle otherwise.
-template <bool OUT_FP32, bool ACC, int FMT, int NJ>
+// l_lo, l_hi: the body works on tiles l_lo .. l_hi-1 of the tile sequence only (l_hi < 0: all of them).
+// HALVES (narrow tile only): tiles_n and the sequence are those of the 256 x 256 grid, and every one of those
+// tiles is worked on as two 256 x 128 tiles, left half then right half: the part-filled last round of a launch
+// that ran its whole rounds on 256 x 256 tiles.
+template <bool OUT_FP32, bool ACC, int FMT, int NJ, bool HALVES = false>
 __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, const uint8_t *__restrict__ as,
                                                const uint8_t *__restrict__ bq, const uint8_t *__restrict__ bs,
                                                int64_t C, void *__restrict__ out, int64_t ld, int tiles_m,
                                                int tiles_n, const uint32_t wg, const uint32_t nwg,
-                                               uint8_t *const smem, const uint32_t lds0)
+                                               uint8_t *const smem, const uint32_t lds0, const int l_lo = 0,
+                                               const int l_hi = -1)
 {
+    static_assert(!HALVES || NJ == 2, "only the narrow tile works on halves of 256 x 256 tiles");
 
     static_assert(NJ == 4 || (NJ == 2 && FMT == 0), "the narrow tile is built for E2M1 operands only");
     constexpr int TILE_N = 64 * NJ;          // B rows (output columns) per tile
@@ -245,20 +251,21 @@ __device__ __forceinline__ void gemm_tile_body(const uint8_t *__restrict__ aq, c
     // their number, so the tiles in flight on one XCD are consecutive in the sequence, and the
     // sequence goes through the tile grid in groups of GROUP_M tile rows: those tiles share
     // A and B panels in the XCD's L2.
-    const int T = tiles_m * tiles_n, G = (int)nwg;
+    const int T = ((l_hi < 0 ? tiles_m * tiles_n : l_hi) - l_lo) * (HALVES ? 2 : 1), G = (int)nwg;
     const int xcd = wg & 7, lw = wg >> 3;
     const int nwg_x = (G - xcd + 7) >> 3;                      // workgroups living on this XCD
     const int per = T >> 3, rem = T & 7;
     const int count_x = per + (xcd < rem ? 1 : 0);             // tiles owned by this XCD
     const int start_x = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
     auto tile_src = [&](int lloc) {
-        const int L = start_x + lloc;
+        const int Lr = start_x + lloc;                       // position in this body's range
+        const int L = l_lo + (HALVES ? (Lr >> 1) : Lr);      // position in the tile sequence
         const int span = GROUP_M * tiles_n, grp = L / span, first = grp * GROUP_M;
         const int gm = (tiles_m - first) < GROUP_M ? (tiles_m - first) : GROUP_M;
         const int in = L - grp * span;
         TileSrc t;
         t.m0 = (int64_t)(first + in % gm) * TILE;
-        t.n0 = (int64_t)(in / gm) * TILE_N;
+        t.n0 = HALVES ? (int64_t)(in / gm) * TILE + (Lr & 1) * TILE_N : (int64_t)(in / gm) * TILE_N;
         t.a = aq + (t.m0 + wave * 64) * rowbytes;
         t.b = bq + (t.n0 + wave * BROWS) * rowbytes;
         t.as = as + (t.m0 + wave * 64) * nkb;
@@ -749,6 +756,22 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(const TileGemm p)
                                            blockIdx.x, gridDim.x, smem, lds0);
 }
 
+// One launch for a product whose last round of 256 x 256 tiles is at most half full: every workgroup first walks
+// the whole rounds (tiles 0 .. t_main-1 of the sequence) on 256 x 256 tiles, then the remaining tiles are worked on
+// as twice as many 256 x 128 tiles, one per workgroup, so that the compute units that would idle in the last round
+// take half of it.  (Nothing is prefetched across the two phases: the second one fills its pipeline again.)
+template <bool OUT_FP32, bool ACC>
+__global__ __launch_bounds__(256, 1) void gemm_tile_tail_kernel(const TileGemm p, const int t_main)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[LDS_BYTES];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    gemm_tile_body<OUT_FP32, ACC, 0, 4>(p.aq, p.as, p.bq, p.bs, p.C, p.out, p.ld, p.tiles_m, p.tiles_n, blockIdx.x,
+                                        gridDim.x, smem, lds0, 0, t_main);
+    __syncthreads();  // (every wave is done with the LDS of the first phase)
+    gemm_tile_body<OUT_FP32, ACC, 0, 2, true>(p.aq, p.as, p.bq, p.bs, p.C, p.out, p.ld, p.tiles_m, p.tiles_n,
+                                              blockIdx.x, gridDim.x, smem, lds0, t_main, p.tiles_m * p.tiles_n);
+}
+
 // Two independent GEMMs in one launch of 256 workgroups (Dgrad and Wgrad of one layer): on every XCD the
 // first n0 of its 32 workgroups work on p0, the others on p1, each set walking its own problem's tiles.
 // The CUs are split in proportion to the work, so both problems end on full rounds of tiles.  Measured on
@@ -863,29 +886,44 @@ static hipError_t launch_tiled_f(const GemmArgs &g, hipStream_t st)
     return hipGetLastError();
 }
 
+// whole rounds on 256 x 256 tiles, then the last round's tiles in halves (see gemm_tile_tail_kernel)
+static hipError_t launch_tiled_tail(const GemmArgs &g, int64_t main_tiles, hipStream_t st)
+{
+    const TileGemm p = tile_args(g);
+    dim3 grid((unsigned)device_cus());
+    if (g.out_fp32) {
+        if (g.accumulate)
+            hipLaunchKernelGGL((gemm_tile_tail_kernel<true, true>), grid, dim3(256), 0, st, p, (int)main_tiles);
+        else
+            hipLaunchKernelGGL((gemm_tile_tail_kernel<true, false>), grid, dim3(256), 0, st, p, (int)main_tiles);
+    } else {
+        hipLaunchKernelGGL((gemm_tile_tail_kernel<false, false>), grid, dim3(256), 0, st, p, (int)main_tiles);
+    }
+    return hipGetLastError();
+}
+
 // Which kernels a GEMM is cut into (host logic only: no device is touched; cus = compute units of the device).
 // Whole 256 x 256 tiles run on the tiled kernel, except where that would leave compute units idle (E2M1 operands):
 //   * fewer tiles than compute units: 256 x 128 tiles (twice as many);
-//   * a last round of tiles at most half full (and at most three rounds in all): the tile rows that make up whole
-//     rounds run on 256 x 256 tiles, the remaining tile rows on 256 x 128 tiles in a second launch;
+//   * a last round of tiles at most half full behind at most four whole rounds: the whole rounds run on 256 x 256
+//     tiles and, in the same launch, the tiles of the last round as twice as many 256 x 128 tiles (GEMM_TILED_256_TAIL_128, main_tiles = the tiles of
+//     the whole rounds);
 //   * a column count in whole 128s but not 256s: 256 x 128 tiles throughout.
 // Ragged row or column counts: the 256-aligned interior as above, the right and bottom edge strips (less than one
 // tile wide) on the any-shape kernel; everything else on the any-shape kernel.
 static void plan_tiled(const GemmArgs &g, int64_t r0, int64_t rows, int64_t cols, int64_t cus, GemmPlan &plan)
 {
-    auto add = [&](int kind, int64_t rr0, int64_t rr) { plan.part[plan.n++] = GemmPart{kind, rr0, rr, 0, cols}; };
-    if (g.a_fmt) return add(GEMM_TILED_256, r0, rows);
-    const int64_t tiles_m = rows / TILE, tiles_n = cols / TILE, T = tiles_m * tiles_n;
-    if (T < cus) return add(GEMM_TILED_128, r0, rows);
-    const int64_t rounds = T / cus, rem = T % cus;
-    if (rem != 0 && 2 * rem <= cus && rounds <= 2) {
-        const int64_t m_main = rounds * cus / tiles_n;  // tile rows that fit into the whole rounds
-        if (m_main >= 1 && m_main < tiles_m) {
-            add(GEMM_TILED_256, r0, m_main * TILE);
-            return add(GEMM_TILED_128, r0 + m_main * TILE, rows - m_main * TILE);
-        }
-    }
-    add(GEMM_TILED_256, r0, rows);
+    auto add = [&](int kind, int64_t main_tiles) {
+        plan.part[plan.n++] = GemmPart{kind, r0, rows, 0, cols, main_tiles};
+    };
+    if (g.a_fmt) return add(GEMM_TILED_256, 0);
+    const int64_t T = (rows / TILE) * (cols / TILE);
+    if (T < cus) return add(GEMM_TILED_128, 0);
+    // (measured: 2 to 5 % on one to three and a half rounds; with more whole rounds in front the second pipeline fill
+    // costs as much as the halves save)
+    const int64_t rem = T % cus;
+    if (rem != 0 && 2 * rem <= cus && T / cus <= 4) return add(GEMM_TILED_256_TAIL_128, T - rem);
+    add(GEMM_TILED_256, 0);
 }
 
 GemmPlan plan_gemm(const GemmArgs &g, int cus)
@@ -895,17 +933,17 @@ GemmPlan plan_gemm(const GemmArgs &g, int cus)
     if (tile_eligible(g)) {
         plan_tiled(g, 0, g.Ra, g.Rb, cus, plan);
     } else if (tile_eligible(g, TILE / 2)) {
-        plan.part[plan.n++] = GemmPart{GEMM_TILED_128, 0, g.Ra, 0, g.Rb};
+        plan.part[plan.n++] = GemmPart{GEMM_TILED_128, 0, g.Ra, 0, g.Rb, 0};
     } else {
         const int64_t ra = g.Ra / TILE * TILE, rb = g.Rb / TILE * TILE;
         // (the interior starts at offset 0 of every array, so it keeps the alignment of the whole problem; the
         // any-shape kernel asks none of the strips' output pointers)
         if (ra > 0 && rb > 0 && tile_eligible(sub_block(g, 0, ra, 0, rb))) {
             plan_tiled(g, 0, ra, rb, cus, plan);
-            if (g.Rb > rb) plan.part[plan.n++] = GemmPart{GEMM_ANY, 0, g.Ra, rb, g.Rb - rb};
-            if (g.Ra > ra) plan.part[plan.n++] = GemmPart{GEMM_ANY, ra, g.Ra - ra, 0, rb};
+            if (g.Rb > rb) plan.part[plan.n++] = GemmPart{GEMM_ANY, 0, g.Ra, rb, g.Rb - rb, 0};
+            if (g.Ra > ra) plan.part[plan.n++] = GemmPart{GEMM_ANY, ra, g.Ra - ra, 0, rb, 0};
         } else {
-            plan.part[plan.n++] = GemmPart{GEMM_ANY, 0, g.Ra, 0, g.Rb};
+            plan.part[plan.n++] = GemmPart{GEMM_ANY, 0, g.Ra, 0, g.Rb, 0};
         }
     }
     return plan;
@@ -922,6 +960,8 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st)
             e = launch_any(h, st);
         else if (p.kind == GEMM_TILED_128)
             e = launch_tiled_f<0, 2>(h, st);
+        else if (p.kind == GEMM_TILED_256_TAIL_128)
+            e = launch_tiled_tail(h, p.main_tiles, st);
         else
             e = g.a_fmt ? launch_tiled_f<1, 4>(h, st) : launch_tiled_f<0, 4>(h, st);
         if (e != hipSuccess) return e;

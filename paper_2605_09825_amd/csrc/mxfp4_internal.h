@@ -53,11 +53,13 @@ struct GemmArgs {
 };
 
 // The kernels one GEMM is cut into: the tiled kernel on 256 x 256 or on 256 x 128 tiles for whole-tile blocks of the
-// output, the any-shape kernel for edge strips and everything else.  At most four parts.
-enum GemmKind { GEMM_ANY = 0, GEMM_TILED_256 = 1, GEMM_TILED_128 = 2 };
+// output (one launch may run whole rounds of 256 x 256 tiles and then the last round in 256 x 128 halves), the
+// any-shape kernel for edge strips and everything else.  At most four parts.
+enum GemmKind { GEMM_ANY = 0, GEMM_TILED_256 = 1, GEMM_TILED_128 = 2, GEMM_TILED_256_TAIL_128 = 3 };
 struct GemmPart {
     int kind;
     int64_t r0, rows, c0, cols;  // block of the output: rows of A, rows of B
+    int64_t main_tiles;          // GEMM_TILED_256_TAIL_128: tiles on 256 x 256 before the rest runs in halves; else 0
 };
 struct GemmPlan {
     int n;

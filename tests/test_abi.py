@@ -244,36 +244,40 @@ def test_static_scratch_forward_argument_errors(L):
 
 def test_gemm_plan_host_logic(L):
     # which kernels a product is cut into (256 compute units): no device is touched
-    A, T256, T128 = mx.GEMM_ANY, mx.GEMM_TILED_256, mx.GEMM_TILED_128
+    A, T256, T128, TAIL = mx.GEMM_ANY, mx.GEMM_TILED_256, mx.GEMM_TILED_128, mx.GEMM_TILED_256_TAIL_128
     plan = mx.mxfp4_gemm_plan
     # the headline GEMMs: 768 and 512 tiles = whole rounds of 256 x 256 tiles
-    assert plan(8192, 6144, 4096) == [(T256, 0, 8192, 0, 6144)]
-    assert plan(8192, 4096, 6144) == [(T256, 0, 8192, 0, 4096)]
-    # its Wgrad, 384 tiles: one whole round on 256 x 256 tiles, the other 8 tile rows on 256 x 128 tiles
-    assert plan(6144, 4096, 8192) == [(T256, 0, 4096, 0, 4096), (T128, 4096, 2048, 0, 4096)]
+    assert plan(8192, 6144, 4096) == [(T256, 0, 8192, 0, 6144, 0)]
+    assert plan(8192, 4096, 6144) == [(T256, 0, 8192, 0, 4096, 0)]
+    # its Wgrad, 384 tiles: one whole round on 256 x 256 tiles, then the other 128 in halves, in one launch
+    assert plan(6144, 4096, 8192) == [(TAIL, 0, 6144, 0, 4096, 256)]
     # fewer tiles than compute units (Llama's k / v projections), columns in whole 128s only
-    assert plan(8192, 1024, 4096) == [(T128, 0, 8192, 0, 1024)]
-    assert plan(1024, 4096, 8192) == [(T128, 0, 1024, 0, 4096)]
-    assert plan(4352, 2176, 1280) == [(T128, 0, 4352, 0, 2176)]
-    # three and a half rounds: too many rounds for the split to pay; a last round more than half full: no split
-    assert plan(4096, 14336, 16384) == [(T256, 0, 4096, 0, 14336)]
-    assert plan(256 * 28, 256 * 16, 4096) == [(T256, 0, 256 * 28, 0, 256 * 16)]        # 448 tiles: 192 in the last
-    # 289 tiles (17 x 17): 15 tile rows in the whole round, 2 on narrow tiles
-    assert plan(4352, 4352, 1024) == [(T256, 0, 3840, 0, 4352), (T128, 3840, 512, 0, 4352)]
+    assert plan(8192, 1024, 4096) == [(T128, 0, 8192, 0, 1024, 0)]
+    assert plan(1024, 4096, 8192) == [(T128, 0, 1024, 0, 4096, 0)]
+    assert plan(4352, 2176, 1280) == [(T128, 0, 4352, 0, 2176, 0)]
+    # three and a half rounds (the Wgrad stress shape): three rounds whole, the last in halves
+    assert plan(4096, 14336, 16384) == [(TAIL, 0, 4096, 0, 14336, 768)]
+    # more than four whole rounds in front (1320 tiles), or a last round more than half full: no halves
+    assert plan(256 * 40, 256 * 33, 2048) == [(T256, 0, 256 * 40, 0, 256 * 33, 0)]
+    assert plan(256 * 28, 256 * 16, 4096) == [(T256, 0, 256 * 28, 0, 256 * 16, 0)]     # 448 tiles: 192 in the last
+    # 289 tiles (17 x 17): 33 in the last round
+    assert plan(4352, 4352, 1024) == [(TAIL, 0, 4352, 0, 4352, 256)]
     # ragged edges: tiled interior + strips on the any-shape kernel
-    assert plan(8224, 6144, 4096) == [(T256, 0, 8192, 0, 6144), (A, 8192, 32, 0, 6144)]
-    assert plan(300, 520, 1024) == [(T128, 0, 256, 0, 512), (A, 0, 300, 512, 8), (A, 256, 44, 0, 512)]
+    assert plan(8224, 6144, 4096) == [(T256, 0, 8192, 0, 6144, 0), (A, 8192, 32, 0, 6144, 0)]
+    assert plan(300, 520, 1024) == [(T128, 0, 256, 0, 512, 0), (A, 0, 300, 512, 8, 0), (A, 256, 44, 0, 512, 0)]
+    assert plan(6144 + 5, 4096, 8192) == [(TAIL, 0, 6144, 0, 4096, 256), (A, 6144, 5, 0, 4096, 0)]
     # contraction too short or not in whole stages, mixed formats, misaligned rows: any-shape kernel
-    assert plan(512, 512, 512) == [(A, 0, 512, 0, 512)]
-    assert plan(512, 512, 1024 + 32) == [(A, 0, 512, 0, 512)]
-    assert plan(512, 512, 2048, mx.FMT_E4M3, mx.FMT_E2M1) == [(A, 0, 512, 0, 512)]
-    assert plan(512, 512, 2048, ld_out=516) == [(A, 0, 512, 0, 512)]
+    assert plan(512, 512, 512) == [(A, 0, 512, 0, 512, 0)]
+    assert plan(512, 512, 1024 + 32) == [(A, 0, 512, 0, 512, 0)]
+    assert plan(512, 512, 2048, mx.FMT_E4M3, mx.FMT_E2M1) == [(A, 0, 512, 0, 512, 0)]
+    assert plan(512, 512, 2048, ld_out=516) == [(A, 0, 512, 0, 512, 0)]
     # MXFP8 stays on 256 x 256 tiles; a smaller chip changes the rounds
-    assert plan(512, 512, 2048, mx.FMT_E4M3, mx.FMT_E4M3) == [(T256, 0, 512, 0, 512)]
-    assert plan(6144, 4096, 8192, compute_units=128) == [(T256, 0, 6144, 0, 4096)]
+    assert plan(512, 512, 2048, mx.FMT_E4M3, mx.FMT_E4M3) == [(T256, 0, 512, 0, 512, 0)]
+    assert plan(6144, 4096, 8192, mx.FMT_E4M3, mx.FMT_E4M3) == [(T256, 0, 6144, 0, 4096, 0)]
+    assert plan(6144, 4096, 8192, compute_units=128) == [(T256, 0, 6144, 0, 4096, 0)]
     assert plan(0, 16, 32) == []
     n = ctypes.c_int(0)
-    parts = (ctypes.c_int64 * 20)()
+    parts = (ctypes.c_int64 * 24)()
     assert L.mxfp4_gemm_plan(16, 16, 48, 0, 0, 16, 256, ctypes.byref(n), parts) == mx.ESHAPE
     assert L.mxfp4_gemm_plan(16, 16, 32, 0, 0, 16, 0, ctypes.byref(n), parts) == mx.EINVAL
     assert L.mxfp4_gemm_plan(16, 16, 32, 7, 0, 16, 256, ctypes.byref(n), parts) == mx.EINVAL

@@ -283,11 +283,13 @@ def test_narrow_tiles_whole_output(shape):
     assert torch.equal(canvas[:Ra, :Rb], f32 + f32)
 
 
-@pytest.mark.parametrize("shape", [(6144, 4096, 2048), (256 * 40, 256 * 8, 1024)])
+@pytest.mark.parametrize("shape", [(6144, 4096, 2048), (256 * 40, 256 * 8, 1024), (4096, 14336, 1024)])
 def test_part_filled_last_round_runs_on_narrow_tiles(shape):
-    # 384 and 320 tiles of 256 x 256 on 256 compute units: the tile rows of the whole round(s) run on 256 x 256
-    # tiles, the rest on 256 x 128 tiles in a second launch; every element of the output against the oracle
+    # 384, 320 and 896 tiles of 256 x 256 on 256 compute units: the whole rounds run on 256 x 256 tiles, the rest in
+    # halves on 256 x 128 tiles in the same launch (896 tiles: the cut after 768 falls inside a row of 56 tiles);
+    # every element of the output against the oracle, also when the product is added to the output
     Ra, Rb, C = shape
+    assert mx.mxfp4_gemm_plan(Ra, Rb, C)[0][0] == mx.GEMM_TILED_256_TAIL_128
     rng = np.random.default_rng(Ra * 3 + Rb + C)
     aq, as_ = rand_operand(rng, Ra, C)
     bq, bs = rand_operand(rng, Rb, C)
@@ -296,6 +298,9 @@ def test_part_filled_last_round_runs_on_narrow_tiles(shape):
     b16 = run_gemm(aq, as_, bq, bs, out_dtype=mx.OUT_BF16)
     assert_close(f32.cpu().numpy(), want, absum)
     assert torch.equal(b16, f32.to(torch.bfloat16))
+    acc = torch.full((Ra, Rb), 0.25, dtype=torch.float32, device="cuda:0")
+    run_gemm(aq, as_, bq, bs, out=acc, out_dtype=mx.OUT_FP32, accumulate=True)
+    assert torch.equal(acc, f32 + 0.25)
 
 
 def test_config2_shape_every_tile():

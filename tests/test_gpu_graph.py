@@ -101,7 +101,7 @@ def test_recorded_forward_on_the_static_scratch_replays_bit_exactly():
 
 
 def test_recorded_gemm_with_a_part_filled_last_round_replays_bit_exactly():
-    # 320 tiles of 256 x 256 on 256 compute units: two launches (256 x 256 tiles, then 256 x 128 tiles on the rest)
+    # 320 tiles of 256 x 256 on 256 compute units: one round of 256 x 256 tiles, then 256 x 128 tiles on the rest
     Ra, Rb, C = 256 * 40, 256 * 8, 1024
     dev = "cuda:0"
     g = torch.Generator(device=dev)

@@ -454,6 +454,26 @@ static int quantize_operand_pair(const mxfp4_linear_cfg *cfg, const void *x0, in
     return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
 }
 
+// The column-wise MXFP4 quantisations of two dense tensors (W and X of a backward call) in one launch.
+static int quantize_cols_pair(const mxfp4_linear_cfg *cfg, const void *x0, int64_t rows0, int64_t cols0, int st0,
+                              uint8_t *q0, uint8_t *s0, const void *x1, int64_t rows1, int64_t cols1, int st1,
+                              uint8_t *q1, uint8_t *s1, void *hip_stream)
+{
+    int rc = check_quantize(x0, rows0, cols0, cols0, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, q0, s0);
+    if (rc >= 0) return rc;  // (an error; the linear calls pass no empty tensors)
+    rc = check_quantize(x1, rows1, cols1, cols1, MXFP4_AXIS_FIRST, cfg->hadamard, cfg->rounding, q1, s1);
+    if (rc >= 0) return rc;
+    const int64_t groups = ((cols0 + 127) / 128) * ((rows0 / 32 + 7) / 8) + ((cols1 + 127) / 128) * ((rows1 / 32 + 7) / 8);
+    if (groups >= (int64_t(1) << 31)) return MXFP4_ESHAPE;  // the two grids share one launch
+    if (!device_ok()) return MXFP4_EDEVICE;
+    const QuantArgs a{static_cast<const uint16_t *>(x0), rows0, cols0, cols0, cfg->hadamard, cfg->rounding,
+                      operand_seed(cfg, st0), q0, s0};
+    const QuantArgs b{static_cast<const uint16_t *>(x1), rows1, cols1, cols1, cfg->hadamard, cfg->rounding,
+                      operand_seed(cfg, st1), q1, s1};
+    hipError_t e = launch_quantize_cols(a, static_cast<hipStream_t>(hip_stream), &b);
+    return e == hipSuccess ? MXFP4_OK : MXFP4_EDEVICE;
+}
+
 // Dgrad and Wgrad of one layer: two GEMMs on the same stream that do not depend on each other.
 static int gemm_pair(const GemmArgs &g0, int dt0, const GemmArgs &g1, int dt1, void *hip_stream)
 {
@@ -585,15 +605,22 @@ int mxfp4_linear_bwd(const void *dy, const void *x, const void *w, void *dx, voi
     rc = quantize_operand(cfg, dy, M, N, F.dgrad, STREAM_DY, dx ? ws + L.gq : nullptr, dx ? ws + L.gs : nullptr,
                           F.wgrad, STREAM_DYT, dw ? ws + L.gtq : nullptr, dw ? ws + L.gts : nullptr, hip_stream);
     if (rc != MXFP4_OK) return rc;
-    if (dx) {
-        rc = quantize_operand(cfg, w, N, K, 0, 0, nullptr, nullptr, F.dgrad, STREAM_WT, ws + L.wtq, ws + L.wts,
-                              hip_stream);
+    if (dx && dw && F.dgrad == MXFP4_FMT_E2M1 && F.wgrad == MXFP4_FMT_E2M1 && cfg->geometry == MXFP4_GEOM_1D) {
+        // W and X, both column-wise in MXFP4: one launch for the two tensors
+        rc = quantize_cols_pair(cfg, w, N, K, STREAM_WT, ws + L.wtq, ws + L.wts, x, M, K, STREAM_XT, ws + L.xtq,
+                                ws + L.xts, hip_stream);
         if (rc != MXFP4_OK) return rc;
-    }
-    if (dw) {
-        rc = quantize_operand(cfg, x, M, K, 0, 0, nullptr, nullptr, F.wgrad, STREAM_XT, ws + L.xtq, ws + L.xts,
-                              hip_stream);
-        if (rc != MXFP4_OK) return rc;
+    } else {
+        if (dx) {
+            rc = quantize_operand(cfg, w, N, K, 0, 0, nullptr, nullptr, F.dgrad, STREAM_WT, ws + L.wtq, ws + L.wts,
+                                  hip_stream);
+            if (rc != MXFP4_OK) return rc;
+        }
+        if (dw) {
+            rc = quantize_operand(cfg, x, M, K, 0, 0, nullptr, nullptr, F.wgrad, STREAM_XT, ws + L.xtq, ws + L.xts,
+                                  hip_stream);
+            if (rc != MXFP4_OK) return rc;
+        }
     }
     const GemmArgs gd{ws + L.gq, ws + L.gs, ws + L.wtq, ws + L.wts, M, K, N, dx, K, cfg->dx_dtype == MXFP4_OUT_FP32, 0,
                       F.dgrad, F.dgrad};

@@ -24,7 +24,8 @@ constexpr uint64_t SEED_BASE_MASK = 0xFFFFFFFFFFFFull;
 // blocks along rows (1x32): q[rows][cols/2], s[rows][cols/32]
 hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st);
 // blocks down columns (32x1): q[cols][rows/2], s[cols][rows/32]
-hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st);
+// (b, if not null: a second tensor in the same launch, same hadamard, rounding and base seed)
+hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st, const QuantArgs *b = nullptr);
 // both from one pass over x: q, s as launch_quantize_cols; q_row, s_row as launch_quantize_rows
 // (b, if not null: a second tensor in the same launch, same hadamard, rounding and seed; the two grids together
 // must stay below 2^31 workgroups)

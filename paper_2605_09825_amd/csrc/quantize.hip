@@ -394,7 +394,10 @@ hipError_t launch_quantize_rows(const QuantArgs &a, hipStream_t st)
     }
 }
 
-hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st) { return launch_cols_mode<MODE_COLS>(a, nullptr, st); }
+hipError_t launch_quantize_cols(const QuantArgs &a, hipStream_t st, const QuantArgs *b)
+{
+    return launch_cols_mode<MODE_COLS>(a, b, st);
+}
 
 hipError_t launch_quantize_dual(const QuantArgs &a, const QuantArgs *b, hipStream_t st)
 {

@@ -283,8 +283,14 @@ def test_backward_side_by_side_launch_with_mxfp8_stages(fmts):
     dx, dw, ws_b = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg)
     dx1, _, _ = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg, need_dw=False)
     _, dw1, _ = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg, need_dx=False)
+    # ... and with dW accumulated into what the buffer already holds
+    cfg_acc = mx.make_cfg(mx.HAD_DET, mx.RNE, 5, y_dtype=mx.OUT_BF16, dx_dtype=mx.OUT_BF16, dw_dtype=mx.OUT_FP32,
+                          dw_accumulate=True, fprop_format=fF, dgrad_format=fD, wgrad_format=fW)
+    dw_acc = torch.full((N, K), 0.125, dtype=torch.float32, device="cuda:0")
+    dx2, _, _ = mx.mxfp4_linear_bwd(dyg, xg, wg, cfg_acc, dw=dw_acc)
     torch.cuda.synchronize()
     assert torch.equal(dx, dx1) and torch.equal(dw, dw1)
+    assert torch.equal(dx2, dx) and torch.equal(dw_acc, dw + 0.125)
     ops = _slices(ws_b, mx.mxfp4_linear_workspace_layout(M, N, K, True, cfg), [(M, N), (K, N), (N, M), (K, M)],
                   [fD, fD, fW, fW])
     rng = np.random.default_rng(4)

@@ -340,3 +340,46 @@ def test_gemm_pair_equals_the_two_separate_calls(shapes, acc):
     assert torch.equal(out0, want0) and torch.equal(out1, want1)
     ref, absum = oracle.gemm(*(t.cpu().numpy() for t in ops[0]))
     close_bf16(out0.float().cpu().numpy(), ref, absum)
+
+
+@pytest.mark.parametrize("fmt", [mx.FMT_E2M1, mx.FMT_E4M3])
+@pytest.mark.parametrize("shape", [(512, 768, 1024), (512, 640, 1024), (768, 2560, 1024), (4096, 4096, 1024)])
+def test_every_output_variant_of_the_tiled_kernels_agrees_with_the_fp32_result(shape, fmt):
+    # 256 x 128 tiles (MXFP4 below 256 tiles), 256 x 256 tiles (MXFP8; MXFP4 at 256 tiles) and a strided output: the bf16 output is the
+    # rounding of the fp32 output, and the accumulating call adds the fp32 output to what the buffer held, bit for bit
+    Ra, Rb, C = shape
+    rng = np.random.default_rng(Ra + Rb + fmt)
+    if fmt == mx.FMT_E2M1:
+        a, b = rand_operand(rng, Ra, C), rand_operand(rng, Rb, C)
+    else:
+        a = (rng.integers(0, 120, size=(Ra, C), dtype=np.uint8), rng.integers(118, 132, size=(Ra, C // 32), dtype=np.uint8))
+        b = (rng.integers(0, 120, size=(Rb, C), dtype=np.uint8), rng.integers(118, 132, size=(Rb, C // 32), dtype=np.uint8))
+    ops = [gpu(t) for t in a + b]
+    kw = dict(a_format=fmt, b_format=fmt)
+    f32 = mx.mxfp4_gemm(*ops, out_dtype=mx.OUT_FP32, **kw)
+    b16 = mx.mxfp4_gemm(*ops, out_dtype=mx.OUT_BF16, **kw)
+    big = torch.full((Ra, Rb + 64), 0.375, dtype=torch.float32, device="cuda:0")
+    mx.mxfp4_gemm(*ops, out=big[:, :Rb], out_dtype=mx.OUT_FP32, accumulate=True, **kw)
+    torch.cuda.synchronize()
+    assert torch.isfinite(f32).all()
+    assert torch.equal(b16, f32.to(torch.bfloat16))
+    assert torch.equal(big[:, :Rb], f32 + 0.375) and bool((big[:, Rb:] == 0.375).all())
+
+
+@pytest.mark.parametrize("dt0,dt1,acc1", [(mx.OUT_BF16, mx.OUT_BF16, False), (mx.OUT_BF16, mx.OUT_FP32, False),
+                                          (mx.OUT_BF16, mx.OUT_FP32, True), (mx.OUT_FP32, mx.OUT_BF16, False),
+                                          (mx.OUT_FP32, mx.OUT_FP32, False), (mx.OUT_FP32, mx.OUT_FP32, True)])
+def test_every_output_variant_of_the_side_by_side_launch(dt0, dt1, acc1):
+    # two problems of 128 tiles each: side by side on 128 compute units each; every combination of output types
+    shapes = ((2048, 4096, 1024), (4096, 2048, 1280))
+    rng = np.random.default_rng(dt0 * 4 + dt1 * 2 + acc1)
+    ops = [tuple(gpu(t) for t in rand_operand(rng, Ra, C) + rand_operand(rng, Rb, C)) for Ra, Rb, C in shapes]
+    (a0q, a0s, b0q, b0s), (a1q, a1s, b1q, b1s) = ops
+    t = lambda d: torch.float32 if d == mx.OUT_FP32 else torch.bfloat16
+    base1 = torch.full((shapes[1][0], shapes[1][1]), 0.5, dtype=t(dt1), device="cuda:0")
+    want0 = mx.mxfp4_gemm(a0q, a0s, b0q, b0s, out_dtype=dt0)
+    want1 = mx.mxfp4_gemm(a1q, a1s, b1q, b1s, out=base1.clone(), out_dtype=dt1, accumulate=acc1)
+    out0, out1 = torch.empty_like(want0), base1.clone()
+    mx.mxfp4_gemm_pair((a0q, a0s), (b0q, b0s), out0, (a1q, a1s), (b1q, b1s), out1, accumulate1=acc1)
+    torch.cuda.synchronize()
+    assert torch.equal(out0, want0) and torch.equal(out1, want1)
